@@ -1,0 +1,254 @@
+"""CPU oracle (test infrastructure) for OOMB's paged sparse attention hot path.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package.  It wraps ``oomb_oracle.c`` (plain C, compiled twice: float and
+double arithmetic) through ctypes and exposes numpy-in / numpy-out functions.
+It shares nothing with the HIP path.
+
+Paper passages followed: Sec. 3 Eq. 2-3 (chunk attends to the growing KV cache,
+KV gradients accumulate), Sec. 4.1 (paged K/V and gradient pools), Sec. 4.2
+(page-mean keys, query-aggregated page scores, top-K pages, indices reused by
+the backward pass).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_BUILD = os.path.join(_HERE, "_build")
+_SRC = os.path.join(_HERE, "oomb_oracle.c")
+
+
+def build(force: bool = False) -> None:
+    """Compile the oracle for float and double arithmetic (gcc, OpenMP)."""
+    os.makedirs(_BUILD, exist_ok=True)
+    for name, real in (("f32", "float"), ("f64", "double")):
+        out = os.path.join(_BUILD, f"liboomb_oracle_{name}.so")
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O2", "-ftree-vectorize", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               f"-DREAL={real}", "-o", out, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("chunk_len", ctypes.c_int32), ("in_is_bf16", ctypes.c_int32),
+                ("ctx_len", ctypes.c_int64), ("sm_scale", ctypes.c_double)]
+
+
+@dataclass
+class Shape:
+    """Problem shape in the paper's notation (Sec. 4.2): C = m*P query tokens,
+    N = n*P tokens reachable through the page table (the chunk included)."""
+    Hq: int
+    Hkv: int
+    D: int
+    P: int
+    C: int
+    N: int
+    sm_scale: float
+
+    @property
+    def n(self) -> int:
+        return self.N // self.P
+
+    @property
+    def m(self) -> int:
+        return self.C // self.P
+
+    @property
+    def n_past(self) -> int:
+        return self.n - self.m
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+
+_libs: dict = {}
+
+
+def _lib(prec: str):
+    if prec not in _libs:
+        build()
+        lib = ctypes.CDLL(os.path.join(_BUILD, f"liboomb_oracle_{prec}.so"))
+        lib.oomb_oracle_row_probs.restype = ctypes.c_int64
+        lib.oomb_oracle_real_bytes.restype = ctypes.c_int
+        assert lib.oomb_oracle_real_bytes() == (4 if prec == "f32" else 8)
+        _libs[prec] = lib
+    return _libs[prec]
+
+
+def _real(prec: str):
+    return np.float32 if prec == "f32" else np.float64
+
+
+def _ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _inputs(prec, *arrays):
+    """Inputs are either all uint16 (bf16 bit patterns) or floating arrays that
+    are converted to the oracle's arithmetic type."""
+    bf = [a.dtype == np.uint16 for a in arrays]
+    if all(bf):
+        return 1, [np.ascontiguousarray(a) for a in arrays]
+    if any(bf):
+        raise ValueError("mix of bf16 and floating inputs")
+    return 0, [np.ascontiguousarray(a, dtype=_real(prec)) for a in arrays]
+
+
+def _desc(sh: Shape, is_bf16: int) -> _Desc:
+    assert sh.Hq % sh.Hkv == 0 and sh.C % sh.P == 0 and sh.N % sh.P == 0 and sh.N >= sh.C
+    return _Desc(sh.Hq, sh.Hkv, sh.D, sh.P, sh.C, is_bf16, sh.N, float(sh.sm_scale))
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _sel_args(sel, sel_count):
+    if sel is None:
+        return None, None, 0
+    sel = _i32(sel)
+    return sel, _i32(sel_count), int(sel.shape[1])
+
+
+def page_score_topk(sh: Shape, q, k_pool, page_table, top_k: int):
+    """Returns (sel [Hkv][top_k + m] int32, padded with -1; sel_count [Hkv];
+    scores [Hkv][n_past] float32).  fp32 arithmetic in a fixed order."""
+    bf, (q, k_pool) = _inputs("f32", q, k_pool)
+    pt = _i32(page_table)
+    assert pt.shape[0] >= sh.n
+    sel = np.full((sh.Hkv, top_k + sh.m), -1, dtype=np.int32)
+    cnt = np.zeros(sh.Hkv, dtype=np.int32)
+    scores = np.zeros((sh.Hkv, max(sh.n_past, 0)), dtype=np.float32)
+    d = _desc(sh, bf)
+    _lib("f32").oomb_oracle_page_score_topk(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(pt),
+                                            ctypes.c_int32(top_k), _ptr(sel), _ptr(cnt), _ptr(scores))
+    return sel, cnt, scores
+
+
+def attn_fwd(sh: Shape, q, k_pool, v_pool, page_table, sel=None, sel_count=None, rows=None,
+             prec: str = "f32"):
+    """O and LSE.  rows: optional int array [n_rows][2] of (h, i) pairs; then O
+    is [n_rows][D] and LSE [n_rows]; otherwise O [C][Hq][D], LSE [Hq][C]."""
+    bf, (q, k_pool, v_pool) = _inputs(prec, q, k_pool, v_pool)
+    pt = _i32(page_table)
+    sel, cnt, stride = _sel_args(sel, sel_count)
+    rt = _real(prec)
+    if rows is None:
+        o = np.zeros((sh.C, sh.Hq, sh.D), dtype=rt)
+        lse = np.zeros((sh.Hq, sh.C), dtype=rt)
+        nr = 0
+    else:
+        rows = _i32(rows).reshape(-1, 2)
+        nr = rows.shape[0]
+        o = np.zeros((nr, sh.D), dtype=rt)
+        lse = np.zeros((nr,), dtype=rt)
+    d = _desc(sh, bf)
+    _lib(prec).oomb_oracle_attn_fwd(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
+                                    _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(rows),
+                                    ctypes.c_int64(nr), _ptr(o), _ptr(lse))
+    return o, lse
+
+
+def row_probs(sh: Shape, q, k_pool, page_table, h: int, i: int, sel=None, sel_count=None,
+              prec: str = "f32"):
+    """Softmax probabilities of row (h, i) and the token positions they belong to."""
+    bf, (q, k_pool) = _inputs(prec, q, k_pool)
+    pt = _i32(page_table)
+    sel, cnt, stride = _sel_args(sel, sel_count)
+    cap = sh.N
+    p = np.zeros(cap, dtype=_real(prec))
+    tok = np.zeros(cap, dtype=np.int64)
+    d = _desc(sh, bf)
+    nv = _lib(prec).oomb_oracle_row_probs(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(pt), _ptr(sel),
+                                          _ptr(cnt), ctypes.c_int32(stride), ctypes.c_int32(h),
+                                          ctypes.c_int32(i), _ptr(p), _ptr(tok))
+    return p[:nv].copy(), tok[:nv].copy()
+
+
+def delta(sh: Shape, d_o, o, prec: str = "f32"):
+    """Delta[h][i] = <dO[i,h,:], O[i,h,:]>; O is the oracle's own forward output."""
+    bf, (d_o,) = _inputs(prec, d_o)
+    o = np.ascontiguousarray(o, dtype=_real(prec))
+    out = np.zeros((sh.Hq, sh.C), dtype=_real(prec))
+    d = _desc(sh, bf)
+    _lib(prec).oomb_oracle_delta(ctypes.byref(d), _ptr(d_o), _ptr(o), _ptr(out))
+    return out
+
+
+def attn_bwd_dq(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, sel=None, sel_count=None,
+                rows=None, prec: str = "f32"):
+    """dQ ([C][Hq][D], or [n_rows][D] for a row subset).  lse/delta_ are [Hq][C]."""
+    bf, (q, k_pool, v_pool, d_o) = _inputs(prec, q, k_pool, v_pool, d_o)
+    pt = _i32(page_table)
+    sel, cnt, stride = _sel_args(sel, sel_count)
+    rt = _real(prec)
+    lse = np.ascontiguousarray(lse, dtype=rt)
+    delta_ = np.ascontiguousarray(delta_, dtype=rt)
+    assert lse.shape == (sh.Hq, sh.C) and delta_.shape == (sh.Hq, sh.C)
+    if rows is None:
+        dq = np.zeros((sh.C, sh.Hq, sh.D), dtype=rt)
+        nr = 0
+    else:
+        rows = _i32(rows).reshape(-1, 2)
+        nr = rows.shape[0]
+        dq = np.zeros((nr, sh.D), dtype=rt)
+    d = _desc(sh, bf)
+    _lib(prec).oomb_oracle_attn_bwd_dq(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
+                                       _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(lse),
+                                       _ptr(delta_), _ptr(d_o), _ptr(rows), ctypes.c_int64(nr),
+                                       _ptr(dq))
+    return dq
+
+
+def attn_bwd_dkv(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, dk_pool, dv_pool,
+                 sel=None, sel_count=None, units=None, prec: str = "f32"):
+    """Accumulates into dk_pool / dv_pool (arrays of the oracle's arithmetic
+    type, shape of the K/V pools) IN PLACE.  units: optional distinct (g, logical
+    page) pairs [n_units][2]; default every selected page of every KV head."""
+    bf, (q, k_pool, v_pool, d_o) = _inputs(prec, q, k_pool, v_pool, d_o)
+    pt = _i32(page_table)
+    sel, cnt, stride = _sel_args(sel, sel_count)
+    rt = _real(prec)
+    lse = np.ascontiguousarray(lse, dtype=rt)
+    delta_ = np.ascontiguousarray(delta_, dtype=rt)
+    assert dk_pool.dtype == rt and dv_pool.dtype == rt
+    assert dk_pool.flags.c_contiguous and dv_pool.flags.c_contiguous
+    if units is None:
+        nu = 0
+    else:
+        units = _i32(units).reshape(-1, 2)
+        nu = units.shape[0]
+        assert len({(int(a), int(b)) for a, b in units}) == nu, "units must be distinct"
+    d = _desc(sh, bf)
+    _lib(prec).oomb_oracle_attn_bwd_dkv(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
+                                        _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(lse),
+                                        _ptr(delta_), _ptr(d_o), _ptr(units), ctypes.c_int64(nu),
+                                        _ptr(dk_pool), _ptr(dv_pool))
+    return dk_pool, dv_pool
+
+
+def attn_fwd_bwd(sh: Shape, q, k_pool, v_pool, page_table, d_o, sel=None, sel_count=None,
+                 dk_pool=None, dv_pool=None, prec: str = "f32"):
+    """Whole pass on all rows: returns dict(o, lse, delta, dq, dk_pool, dv_pool)."""
+    rt = _real(prec)
+    o, lse = attn_fwd(sh, q, k_pool, v_pool, page_table, sel, sel_count, prec=prec)
+    dl = delta(sh, d_o, o, prec=prec)
+    dq = attn_bwd_dq(sh, q, k_pool, v_pool, page_table, lse, dl, d_o, sel, sel_count, prec=prec)
+    if dk_pool is None:
+        dk_pool = np.zeros(k_pool.shape, dtype=rt)
+    if dv_pool is None:
+        dv_pool = np.zeros(k_pool.shape, dtype=rt)
+    attn_bwd_dkv(sh, q, k_pool, v_pool, page_table, lse, dl, d_o, dk_pool, dv_pool, sel, sel_count,
+                 prec=prec)
+    return dict(o=o, lse=lse, delta=dl, dq=dq, dk_pool=dk_pool, dv_pool=dv_pool)
