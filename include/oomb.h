@@ -1,0 +1,152 @@
+/*
+ * oomb.h — C ABI of the MI355X (gfx950) paged sparse attention library.
+ *
+ * The library implements the per-layer hot path of OOMB's chunk-recurrent
+ * long-context training: attention of one query chunk against a growing paged
+ * KV cache with page-level top-k page selection, forward and backward, the
+ * backward accumulating dK/dV in place into a paged KV-gradient pool.
+ *
+ * Problem statement (paper Sec. 3, Eq. 2-3; Sec. 4.1; Sec. 4.2), notation:
+ *   Hq query heads, Hkv KV heads, G = Hq / Hkv, head dim D, page size P,
+ *   chunk of C = m*P query tokens, N = n*P tokens reachable through the page
+ *   table at call time INCLUDING the chunk's own C tokens as the last m logical
+ *   pages, n_past = n - m.  Query head h reads KV head g = h / G.  Query i of
+ *   the chunk sits at absolute position a_i = N - C + i and sees token t iff
+ *   t <= a_i and logical page t / P is in the selection list of KV head g.
+ *
+ * Memory: EVERY pointer below is DEVICE memory owned by the caller (except the
+ * descriptor, which is host memory read during the call).  The library never
+ * allocates, frees or synchronises; all work is enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream) and the call returns at once.
+ * Layouts (element strides given in the descriptor, D always contiguous):
+ *   Q, O, dO, dQ      [C][Hq][D]       q_tok_stride, q_head_stride
+ *   K/V pools         [n_phys][Hkv][P][D]  pool_page_stride, pool_head_stride, pool_tok_stride
+ *   dK/dV pools       same strides as the K/V pools, element type grad_dtype
+ *   page_table        [n] int32, logical page -> physical page; entries must be
+ *                     distinct and in [0, num_phys_pages) (precondition, not checked
+ *                     on the device)
+ *   LSE               [Hq][C] float, natural log of the sum of exp(scaled logits)
+ *   selection lists   [Hkv][sel_stride] int32 LOGICAL page ids, ascending, distinct,
+ *                     with sel_count[g] valid entries; they must contain the m local
+ *                     pages n_past..n-1 (so that no query row is empty)
+ * All base pointers and strides must keep 16-byte alignment of every D-row.
+ *
+ * Errors: every entry point validates host-visible scalars and pointers before
+ * anything is launched and returns a status; on any status other than OOMB_OK
+ * nothing was enqueued.  OOMB_ERR_LAUNCH reports a failed kernel launch.
+ */
+#ifndef OOMB_H_
+#define OOMB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OOMB_OK = 0,
+  OOMB_ERR_INVALID_ARG = 1, /* NULL pointer, non-divisible sizes, bad stride/alignment */
+  OOMB_ERR_UNSUPPORTED = 2, /* shape / dtype combination with no kernel */
+  OOMB_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than oomb_workspace_bytes() */
+  OOMB_ERR_LAUNCH = 4       /* HIP reported a launch error */
+} oomb_status;
+
+typedef enum { OOMB_F32 = 0, OOMB_BF16 = 1 } oomb_dtype;
+
+typedef enum { OOMB_OP_SCORE_TOPK = 0, OOMB_OP_ATTN_FWD = 1, OOMB_OP_ATTN_BWD = 2 } oomb_op;
+
+typedef struct {
+  int32_t n_q_heads;   /* Hq */
+  int32_t n_kv_heads;  /* Hkv, divides Hq */
+  int32_t head_dim;    /* D: 64 or 128 */
+  int32_t page_size;   /* P: power of two, 16..128 */
+  int32_t chunk_len;   /* C, multiple of P */
+  int32_t dtype;       /* oomb_dtype of Q, K, V, O, dO, dQ */
+  int32_t grad_dtype;  /* oomb_dtype of the dK / dV pools */
+  float sm_scale;      /* logits = sm_scale * <q, k>; > 0 */
+  int64_t ctx_len;     /* N, includes the chunk; multiple of P; N >= C */
+  int64_t pool_page_stride, pool_head_stride, pool_tok_stride; /* elements */
+  int64_t q_tok_stride, q_head_stride;                         /* elements */
+  int64_t num_phys_pages; /* pages in each pool; n <= num_phys_pages */
+} oomb_attn_desc;
+
+/* Bytes of device workspace `op` needs for this descriptor (top_k is read for
+ * OOMB_OP_SCORE_TOPK only).  Returns 0 for an invalid descriptor. */
+size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t op);
+
+/*
+ * Page scoring + top-k page selection (Sec. 4.2: each key page is represented
+ * by the mean of its keys; the chunk's queries are aggregated into one score
+ * per key page; the top-K pages are kept).  Per KV head g:
+ *   qbar[g]     = mean over the C tokens and the G heads of group g of Q
+ *   kbar[g][l]  = mean of the P keys of logical page l (read through page_table)
+ *   score[g][l] = <qbar[g], kbar[g][l]>              for past pages l < n_past
+ * in IEEE binary32 with a fixed operation order (no fused multiply-add):
+ * token sums run left to right, qbar sums query pages (outer) then heads
+ * (inner), the dot product is a stride-halving tree over d.  The k_eff =
+ * min(top_k, n_past) past pages with the largest score are kept, ties going to
+ * the lower logical id (-0 == +0); the m local pages are appended; the list is
+ * written in ascending logical id.  Scores must be finite.
+ *
+ *   q          [C][Hq][D]                        in
+ *   k_pool     K pool                            in
+ *   page_table [n]                               in
+ *   sel_pages  [Hkv][top_k + m] int32            out (entries past sel_count[g] = -1)
+ *   sel_count  [Hkv] int32                       out
+ *   scores_out [Hkv][n_past] float or NULL       out
+ * top_k >= 0.  Returns OOMB_ERR_UNSUPPORTED when n_past exceeds 1,048,576.
+ */
+oomb_status oomb_page_score_topk(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                 const int32_t* page_table, int32_t top_k, int32_t* sel_pages,
+                                 int32_t* sel_count, float* scores_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Paged attention forward (Sec. 4.1 operator over the pages of Sec. 4.2).
+ * For every query head h and chunk row i:
+ *   s_t = sm_scale * <Q[i,h], K[t,g]> over the visible tokens t,
+ *   LSE[h][i] = log sum_t exp(s_t),  O[i,h,:] = sum_t exp(s_t - LSE) V[t,g,:].
+ *   sel_pages == NULL selects every logical page 0..n-1 (dense); then sel_count
+ *   and sel_stride are ignored.
+ *   o   [C][Hq][D] out (overwritten);  lse [Hq][C] float out (overwritten).
+ */
+oomb_status oomb_paged_attn_fwd(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* page_table,
+                                const int32_t* sel_pages, const int32_t* sel_count,
+                                int32_t sel_stride, void* o, float* lse, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Paged attention backward (Sec. 3 Eq. 3: KV gradients of earlier chunks
+ * accumulate over later chunks' backward passes; Sec. 4.1: in-place
+ * accumulation into the paged gradient pool; Sec. 4.2: the forward's page
+ * indices are reused).  With p_t = exp(s_t - LSE), Delta = <dO[i,h], O[i,h]>,
+ * dp_t = <dO[i,h], V[t,g]>, ds_t = p_t (dp_t - Delta):
+ *   dQ[i,h,:]           = sm_scale * sum_t ds_t K[t,g,:]                (overwritten)
+ *   dK pool[t,g,:]     += sm_scale * sum_{h in g} sum_i ds_t Q[i,h,:]    (accumulated)
+ *   dV pool[t,g,:]     += sum_{h in g} sum_i p_t dO[i,h,:]               (accumulated)
+ * at pool[page_table[t / P]][g][t % P][:], for the tokens of the selected pages
+ * only; every other page of the gradient pools is left bit-identical.  The
+ * pools are never zeroed here.  Each (KV head, page) is updated by exactly one
+ * workgroup with plain loads and stores (no atomics), so results do not depend
+ * on scheduling.  `sel_pages` must be the list the forward used; `o` and `lse`
+ * are the forward's outputs.
+ */
+oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* page_table,
+                                const int32_t* sel_pages, const int32_t* sel_count,
+                                int32_t sel_stride, const void* o, const float* lse,
+                                const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+const char* oomb_status_string(int32_t status);
+
+/* major * 10000 + minor * 100 + patch */
+int32_t oomb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OOMB_H_ */

@@ -1,0 +1,162 @@
+"""Python binding of the C-ABI library (include/oomb.h): argument marshalling
+only.  Torch supplies device memory and the stream; every step of the path runs
+in the library's HIP kernels.  Function names mirror the C entry points."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liboomb.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
+F32, BF16 = 0, 1
+OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD = 0, 1, 2
+
+EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
+           "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version"]
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("chunk_len", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("grad_dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+                ("ctx_len", ctypes.c_int64),
+                ("pool_page_stride", ctypes.c_int64), ("pool_head_stride", ctypes.c_int64),
+                ("pool_tok_stride", ctypes.c_int64),
+                ("q_tok_stride", ctypes.c_int64), ("q_head_stride", ctypes.c_int64),
+                ("num_phys_pages", ctypes.c_int64)]
+
+
+class OombError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2602_02108_amd.build "
+                               "or __graft_entry__.build())")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp = ctypes.POINTER(AttnDesc)
+        l.oomb_workspace_bytes.restype = u64
+        l.oomb_workspace_bytes.argtypes = [dp, i32, i32]
+        l.oomb_page_score_topk.restype = i32
+        l.oomb_page_score_topk.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
+        l.oomb_paged_attn_fwd.restype = i32
+        l.oomb_paged_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, u64, vp]
+        l.oomb_paged_attn_bwd.restype = i32
+        l.oomb_paged_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+        l.oomb_status_string.restype = ctypes.c_char_p
+        l.oomb_status_string.argtypes = [i32]
+        l.oomb_version.restype = i32
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().oomb_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().oomb_version())
+
+
+def _dt(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def make_desc(q: torch.Tensor, k_pool: torch.Tensor, ctx_len: int, sm_scale: float,
+              grad_dtype: torch.dtype = torch.float32) -> AttnDesc:
+    """Descriptor from a query chunk [C][Hq][D] and a K pool [n_phys][Hkv][P][D]."""
+    C, Hq, D = q.shape
+    n_phys, Hkv, P, D2 = k_pool.shape
+    assert D == D2 and q.stride(2) == 1 and k_pool.stride(3) == 1
+    return AttnDesc(Hq, Hkv, D, P, C, _dt(q.dtype), _dt(grad_dtype), float(sm_scale), int(ctx_len),
+                    k_pool.stride(0), k_pool.stride(1), k_pool.stride(2), q.stride(0), q.stride(1), n_phys)
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def workspace_bytes(desc: AttnDesc, top_k: int, op: int) -> int:
+    return int(lib().oomb_workspace_bytes(ctypes.byref(desc), int(top_k), int(op)))
+
+
+def _workspace(desc, top_k, op, device, workspace):
+    need = workspace_bytes(desc, top_k, op)
+    if need == 0:
+        raise OombError(ERR_INVALID_ARG, "oomb_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def page_score_topk(desc: AttnDesc, q, k_pool, page_table, top_k: int, sel_pages=None, sel_count=None,
+                    scores_out=None, workspace=None):
+    """oomb_page_score_topk.  Returns (sel_pages [Hkv][top_k + m] int32, sel_count [Hkv] int32)."""
+    m = desc.chunk_len // desc.page_size
+    if sel_pages is None:
+        sel_pages = torch.empty((desc.n_kv_heads, top_k + m), dtype=torch.int32, device=q.device)
+    if sel_count is None:
+        sel_count = torch.empty((desc.n_kv_heads,), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(desc, top_k, OP_SCORE_TOPK, q.device, workspace)
+    st = lib().oomb_page_score_topk(ctypes.byref(desc), _p(q), _p(k_pool), _p(page_table), int(top_k),
+                                    _p(sel_pages), _p(sel_count), _p(scores_out), _p(workspace), nbytes,
+                                    _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_page_score_topk")
+    return sel_pages, sel_count
+
+
+def paged_attn_fwd(desc: AttnDesc, q, k_pool, v_pool, page_table, sel_pages=None, sel_count=None, o=None,
+                   lse=None, workspace=None):
+    """oomb_paged_attn_fwd.  Returns (O [C][Hq][D], LSE [Hq][C] float32)."""
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((desc.n_q_heads, desc.chunk_len), dtype=torch.float32, device=q.device)
+    workspace, nbytes = _workspace(desc, 0, OP_ATTN_FWD, q.device, workspace)
+    stride = 0 if sel_pages is None else int(sel_pages.stride(0))
+    st = lib().oomb_paged_attn_fwd(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
+                                   _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(workspace), nbytes,
+                                   _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_paged_attn_fwd")
+    return o, lse
+
+
+def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, dk_pool, dv_pool,
+                   sel_pages=None, sel_count=None, d_q=None, workspace=None):
+    """oomb_paged_attn_bwd.  Returns dQ; dk_pool / dv_pool are accumulated in place."""
+    if d_q is None:
+        d_q = torch.empty_like(q)
+    workspace, nbytes = _workspace(desc, 0, OP_ATTN_BWD, q.device, workspace)
+    stride = 0 if sel_pages is None else int(sel_pages.stride(0))
+    st = lib().oomb_paged_attn_bwd(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
+                                   _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(d_o), _p(d_q),
+                                   _p(dk_pool), _p(dv_pool), _p(workspace), nbytes, _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_paged_attn_bwd")
+    return d_q

@@ -1,0 +1,196 @@
+// C-ABI entry points: host-side validation and kernel dispatch.  Nothing is
+// allocated, freed or synchronised here; every launch goes to the caller's stream.
+#include <cmath>
+#include <cstdlib>
+
+#include "common.h"
+
+namespace oomb {
+size_t score_workspace_bytes(const Params& p);
+hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel,
+                             int32_t* sel_count, float* scores_out, void* ws, hipStream_t st);
+hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st);
+hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st);
+hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
+bool mfma_supported(const Params& p, bool is_bf16);
+hipError_t launch_fwd_mfma(const Params& p, hipStream_t st);
+hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
+size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
+}  // namespace oomb
+
+using namespace oomb;
+
+namespace {
+
+bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+size_t elem_size(int32_t dt) { return dt == OOMB_BF16 ? 2 : 4; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Kernels without MFMA can be forced for debugging and cross-checks.
+bool force_generic() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = std::getenv("OOMB_FORCE_GENERIC");
+    v = (e && e[0] == '1') ? 1 : 0;
+  }
+  return v == 1;
+}
+
+oomb_status check_desc(const oomb_attn_desc* d, Params* p) {
+  if (!d) return OOMB_ERR_INVALID_ARG;
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads) return OOMB_ERR_INVALID_ARG;
+  if (d->head_dim <= 0 || d->page_size <= 0 || d->chunk_len <= 0 || d->ctx_len <= 0) return OOMB_ERR_INVALID_ARG;
+  if (d->chunk_len % d->page_size || d->ctx_len % d->page_size || d->ctx_len < d->chunk_len)
+    return OOMB_ERR_INVALID_ARG;
+  if ((d->dtype != OOMB_F32 && d->dtype != OOMB_BF16) || (d->grad_dtype != OOMB_F32 && d->grad_dtype != OOMB_BF16))
+    return OOMB_ERR_INVALID_ARG;
+  if (!(d->sm_scale > 0.f) || !std::isfinite(d->sm_scale)) return OOMB_ERR_INVALID_ARG;
+  const size_t es = elem_size(d->dtype), gs = elem_size(d->grad_dtype);
+  const int64_t strides[5] = {d->pool_page_stride, d->pool_head_stride, d->pool_tok_stride, d->q_tok_stride,
+                              d->q_head_stride};
+  for (int64_t s : strides) {
+    if (s < d->head_dim) return OOMB_ERR_INVALID_ARG;
+    if ((s * (int64_t)es) % 16 || (s * (int64_t)gs) % 16) return OOMB_ERR_INVALID_ARG;
+  }
+  if (d->num_phys_pages < d->ctx_len / d->page_size) return OOMB_ERR_INVALID_ARG;
+  if (d->ctx_len / d->page_size > INT32_MAX) return OOMB_ERR_INVALID_ARG;
+  if ((d->head_dim != 64 && d->head_dim != 128) || !is_pow2(d->page_size) || d->page_size < 16 ||
+      d->page_size > 128)
+    return OOMB_ERR_UNSUPPORTED;
+  p->Hq = d->n_q_heads; p->Hkv = d->n_kv_heads; p->G = p->Hq / p->Hkv; p->D = d->head_dim;
+  p->P = d->page_size; p->C = d->chunk_len; p->m = p->C / p->P;
+  p->N = d->ctx_len; p->n = p->N / p->P; p->n_past = p->n - p->m;
+  p->sm_scale = d->sm_scale;
+  p->pool_page_stride = d->pool_page_stride; p->pool_head_stride = d->pool_head_stride;
+  p->pool_tok_stride = d->pool_tok_stride;
+  p->q_tok_stride = d->q_tok_stride; p->q_head_stride = d->q_head_stride;
+  p->grad_is_bf16 = d->grad_dtype == OOMB_BF16;
+  return OOMB_OK;
+}
+
+oomb_status check_list(const Params& p, const int32_t* sel, const int32_t* cnt, int32_t stride,
+                       int32_t* max_len) {
+  if (!sel) {
+    *max_len = (int32_t)p.n;
+    return OOMB_OK;
+  }
+  if (!cnt || stride < p.m) return OOMB_ERR_INVALID_ARG;
+  *max_len = stride < p.n ? stride : (int32_t)p.n;
+  return OOMB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t op) {
+  Params p{};
+  if (check_desc(desc, &p) != OOMB_OK) return 0;
+  switch (op) {
+    case OOMB_OP_SCORE_TOPK:
+      if (top_k < 0) return 0;
+      return score_workspace_bytes(p);
+    case OOMB_OP_ATTN_FWD:
+      return 256;
+    case OOMB_OP_ATTN_BWD: {
+      size_t b = up256((size_t)p.Hq * p.C * sizeof(float));
+      if (mfma_supported(p, desc->dtype == OOMB_BF16)) b += bwd_mfma_workspace_bytes(p, (int32_t)p.n);
+      return b;
+    }
+    default:
+      return 0;
+  }
+}
+
+oomb_status oomb_page_score_topk(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                 const int32_t* page_table, int32_t top_k, int32_t* sel_pages,
+                                 int32_t* sel_count, float* scores_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !page_table || !sel_pages || !sel_count || top_k < 0) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool)) return OOMB_ERR_INVALID_ARG;
+  if (p.n_past > (1 << 20)) return OOMB_ERR_UNSUPPORTED;
+  if (!workspace || workspace_bytes < score_workspace_bytes(p)) return OOMB_ERR_WORKSPACE;
+  p.q = q; p.k_pool = k_pool; p.page_table = page_table;
+  hipError_t e = launch_score_topk(p, desc->dtype == OOMB_BF16, top_k, sel_pages, sel_count, scores_out,
+                                   workspace, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_paged_attn_fwd(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* page_table,
+                                const int32_t* sel_pages, const int32_t* sel_count,
+                                int32_t sel_stride, void* o, float* lse, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !v_pool || !page_table || !o || !lse) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o)) return OOMB_ERR_INVALID_ARG;
+  int32_t max_len = 0;
+  s = check_list(p, sel_pages, sel_count, sel_stride, &max_len);
+  if (s != OOMB_OK) return s;
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
+  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
+  p.o = o; p.lse = lse;
+  const bool bf = desc->dtype == OOMB_BF16;
+  hipError_t e;
+  if (!force_generic() && mfma_supported(p, bf)) e = launch_fwd_mfma(p, (hipStream_t)hip_stream);
+  else e = launch_fwd_generic(p, bf, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* page_table,
+                                const int32_t* sel_pages, const int32_t* sel_count,
+                                int32_t sel_stride, const void* o, const float* lse,
+                                const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !v_pool || !page_table || !o || !lse || !d_o || !d_q || !dk_pool || !dv_pool)
+    return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o) || !aligned16(d_o) ||
+      !aligned16(d_q) || !aligned16(dk_pool) || !aligned16(dv_pool))
+    return OOMB_ERR_INVALID_ARG;
+  int32_t max_len = 0;
+  s = check_list(p, sel_pages, sel_count, sel_stride, &max_len);
+  if (s != OOMB_OK) return s;
+  const bool bf = desc->dtype == OOMB_BF16;
+  const bool use_mfma = !force_generic() && mfma_supported(p, bf);
+  size_t need = up256((size_t)p.Hq * p.C * sizeof(float));
+  const size_t delta_bytes = need;
+  if (use_mfma) need += bwd_mfma_workspace_bytes(p, max_len);
+  if (!workspace || workspace_bytes < need || !aligned16(workspace)) return OOMB_ERR_WORKSPACE;
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
+  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
+  p.o = const_cast<void*>(o); p.lse = const_cast<float*>(lse); p.d_o = d_o; p.d_q = d_q;
+  p.dk_pool = dk_pool; p.dv_pool = dv_pool;
+  p.delta = (float*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = launch_delta(p, bf, st);
+  if (e != hipSuccess) return OOMB_ERR_LAUNCH;
+  if (use_mfma) e = launch_bwd_mfma(p, max_len, (char*)workspace + delta_bytes, st);
+  else e = launch_bwd_generic(p, bf, max_len, st);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+const char* oomb_status_string(int32_t status) {
+  switch (status) {
+    case OOMB_OK: return "ok";
+    case OOMB_ERR_INVALID_ARG: return "invalid argument";
+    case OOMB_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case OOMB_ERR_WORKSPACE: return "workspace missing or too small";
+    case OOMB_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t oomb_version(void) { return 100; }
+
+}  // extern "C"

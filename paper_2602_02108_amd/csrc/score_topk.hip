@@ -1,0 +1,278 @@
+// Page scoring and top-k page selection (paper Sec. 4.2): the mean of each key
+// page is scored against the mean-pooled chunk query of its KV head and the
+// top-K past pages are kept, plus the chunk's own pages.
+//
+// The fp32 operation order is fixed so that scores are reproducible bit for bit:
+//   token sums left to right; qbar sums query pages (outer) then heads (inner);
+//   dot product as a stride-halving tree over d.  No fused multiply-add.
+// The page-mean kernel is HBM-bound: it streams every past key once.
+#include "common.h"
+
+#pragma clang fp contract(off)
+
+namespace oomb {
+
+template <typename T> struct Vec16;  // one 16-byte load worth of elements
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+// Left-to-right sum of `count` rows (row stride `stride` elements) of the VEC
+// elements this lane owns.  Loads are issued U at a time, adds stay in order.
+template <typename T, int U>
+__device__ __forceinline__ void seq_row_sum(const T* base, int64_t stride, int count, float* acc) {
+  constexpr int VEC = Vec16<T>::N;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
+  int t = 0;
+  for (; t + U <= count; t += U) {
+    uint4 r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) r[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + u) * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[VEC];
+      Vec16<T>::unpack(r[u], f);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] = __fadd_rn(acc[v], f[v]);
+    }
+  }
+  for (; t < count; ++t) {
+    uint4 r = *reinterpret_cast<const uint4*>(base + (int64_t)t * stride);
+    float f[VEC];
+    Vec16<T>::unpack(r, f);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = __fadd_rn(acc[v], f[v]);
+  }
+}
+
+// Step S1a: A[h][tau][d] = sum over the P tokens of query page tau of Q.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void qpool_partial_kernel(Params p, float* __restrict__ A) {
+  constexpr int VEC = Vec16<T>::N, LPR = D / VEC, UPB = 256 / LPR;
+  const int unit = blockIdx.x * UPB + threadIdx.x / LPR;
+  const int lr = threadIdx.x % LPR;
+  if (unit >= p.Hq * p.m) return;
+  const int h = unit / p.m, tau = unit % p.m;
+  const T* base = (const T*)p.q + (int64_t)tau * p.P * p.q_tok_stride + (int64_t)h * p.q_head_stride + lr * VEC;
+  float acc[VEC];
+  seq_row_sum<T, 16>(base, p.q_tok_stride, p.P, acc);
+  float* out = A + ((int64_t)h * p.m + tau) * D + lr * VEC;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) out[v] = acc[v];
+}
+
+// Step S1b: qbar[g][d] = (sum over tau (outer), heads of g (inner) of A) * r.
+__global__ void qpool_final_kernel(Params p, const float* __restrict__ A, float* __restrict__ qbar, float r) {
+  const int g = blockIdx.x, d = threadIdx.x;
+  if (d >= p.D) return;
+  float acc = 0.0f;
+  for (int tau = 0; tau < p.m; ++tau)
+    for (int h = g * p.G; h < g * p.G + p.G; ++h)
+      acc = __fadd_rn(acc, A[((int64_t)h * p.m + tau) * p.D + d]);
+  qbar[g * p.D + d] = __fmul_rn(acc, r);
+}
+
+// Steps S2 + S3: one group of LPR lanes walks one (KV head, logical page) tile
+// of the K pool token by token; a wave covers 64 / LPR pages at once.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void page_score_kernel(Params p, const float* __restrict__ qbar,
+                                                         float* __restrict__ scores, float inv_p) {
+  constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PPB = 256 / LPR;
+  const int g = blockIdx.y;
+  const int lr = threadIdx.x % LPR;
+  const int64_t l = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+  const bool active = l < p.n_past;
+  const int64_t lc = active ? l : 0;
+  const T* base = (const T*)p.k_pool + (int64_t)p.page_table[lc] * p.pool_page_stride +
+                  (int64_t)g * p.pool_head_stride + lr * VEC;
+  float x[VEC];
+  seq_row_sum<T, 8>(base, p.pool_tok_stride, p.P, x);
+  const float* qb = qbar + g * D + lr * VEC;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) x[v] = __fmul_rn(qb[v], __fmul_rn(x[v], inv_p));
+  // tree over d: strides D/2 .. VEC cross lanes, then VEC/2 .. 1 inside the lane
+#pragma unroll
+  for (int s = D / 2; s >= VEC; s >>= 1) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) x[v] = __fadd_rn(x[v], __shfl_xor(x[v], s / VEC, 64));
+  }
+#pragma unroll
+  for (int s = VEC / 2; s >= 1; s >>= 1) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v)
+      if (v < s) x[v] = __fadd_rn(x[v], x[v + s]);
+  }
+  if (active && lr == 0) scores[(int64_t)g * p.n_past + l] = x[0];
+}
+
+// Order-preserving map float -> uint32 (larger float = larger key); -0 maps with +0.
+__device__ __forceinline__ uint32_t order_key(float s) {
+  uint32_t b = __float_as_uint(s);
+  if ((b << 1) == 0u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int SELECT_THREADS = 1024;
+
+__device__ __forceinline__ int block_sum(int v, int* smem /*[17]*/) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();  // protects smem reuse across calls
+  if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int tot = 0;
+#pragma unroll
+  for (int w = 0; w < SELECT_THREADS / 64; ++w) tot += smem[w];
+  return tot;
+}
+
+// Step S4.  One workgroup per KV head.  The k-th largest key is found by
+// bisection over its 32 bits (count of keys >= candidate), then the list is
+// emitted in ascending logical id: all keys above the threshold, the lowest-id
+// keys equal to it, and the local pages.
+__global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
+    const float* __restrict__ scores, int64_t n_past, int32_t m, int32_t top_k,
+    int32_t* __restrict__ sel, int32_t* __restrict__ sel_count, int32_t lds_cap) {
+  extern __shared__ uint32_t keys[];  // first min(n_past, lds_cap) keys cached
+  __shared__ int red[SELECT_THREADS / 64 + 1];
+  __shared__ int scan_w[SELECT_THREADS / 64];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const float* sc = scores + (int64_t)g * n_past;
+  const int32_t stride = top_k + m;
+  int32_t* out = sel + (int64_t)g * stride;
+  const int32_t k_eff = (int32_t)(top_k < n_past ? top_k : n_past);
+  const int64_t cached = n_past < lds_cap ? n_past : lds_cap;
+
+  for (int64_t l = tid; l < cached; l += SELECT_THREADS) keys[l] = order_key(sc[l]);
+  __syncthreads();
+  auto key_at = [&](int64_t l) -> uint32_t { return l < cached ? keys[l] : order_key(sc[l]); };
+
+  uint32_t T = 0;
+  int take_eq = 0;
+  if (k_eff > 0) {
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = T | (1u << bit);
+      int c = 0;
+      for (int64_t l = tid; l < n_past; l += SELECT_THREADS) c += key_at(l) >= cand;
+      if (block_sum(c, red) >= k_eff) T = cand;
+    }
+    int c = 0;
+    for (int64_t l = tid; l < n_past; l += SELECT_THREADS) c += key_at(l) > T;
+    take_eq = k_eff - block_sum(c, red);  // how many keys equal to T are kept (lowest ids)
+  }
+
+  // ordered emission: thread t owns the contiguous id range [t*per, (t+1)*per)
+  const int64_t per = (n_past + SELECT_THREADS - 1) / SELECT_THREADS;
+  const int64_t lo = (int64_t)tid * per, hi = (lo + per < n_past) ? lo + per : n_past;
+  int n_eq = 0, n_gt = 0;
+  if (k_eff > 0)
+    for (int64_t l = lo; l < hi; ++l) {
+      const uint32_t k = key_at(l);
+      n_eq += k == T;
+      n_gt += k > T;
+    }
+  // exclusive scans of (n_eq, n_gt) over threads, packed in one 64-bit add
+  unsigned long long v = ((unsigned long long)(uint32_t)n_eq << 32) | (uint32_t)n_gt;
+  unsigned long long incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    unsigned long long nb = __shfl_up(incl, o, 64);
+    if ((tid & 63) >= o) incl += nb;
+  }
+  __shared__ unsigned long long wave_tot[SELECT_THREADS / 64];
+  if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+  __syncthreads();
+  unsigned long long base = 0;
+  for (int w = 0; w < (tid >> 6); ++w) base += wave_tot[w];
+  const unsigned long long excl = base + incl - v;
+  int eq_before = (int)(excl >> 32);
+  int gt_before = (int)(excl & 0xffffffffu);
+  if (k_eff > 0) {
+    // position = kept keys with lower id = gt_before + min(eq_before, take_eq)
+    int pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
+    for (int64_t l = lo; l < hi; ++l) {
+      const uint32_t k = key_at(l);
+      if (k > T) {
+        out[pos++] = (int32_t)l;
+      } else if (k == T) {
+        if (eq_before < take_eq) out[pos++] = (int32_t)l;
+        ++eq_before;
+      }
+    }
+  }
+  for (int32_t j = tid; j < m; j += SELECT_THREADS) out[k_eff + j] = (int32_t)(n_past + j);
+  for (int32_t j = k_eff + m + tid; j < stride; j += SELECT_THREADS) out[j] = -1;
+  if (tid == 0) sel_count[g] = k_eff + m;
+  (void)scan_w;
+}
+
+template <typename T, int D>
+static void launch_scoring(const Params& p, float* A, float* qbar, float* scores, hipStream_t st) {
+  constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PER_BLOCK = 256 / LPR;
+  const int units = p.Hq * p.m;
+  qpool_partial_kernel<T, D><<<dim3((units + PER_BLOCK - 1) / PER_BLOCK), dim3(256), 0, st>>>(p, A);
+  const float r = 1.0f / (float)((int64_t)p.C * p.G);
+  qpool_final_kernel<<<dim3(p.Hkv), dim3(D), 0, st>>>(p, A, qbar, r);
+  if (p.n_past > 0) {
+    const float inv_p = 1.0f / (float)p.P;
+    dim3 grid((unsigned)((p.n_past + PER_BLOCK - 1) / PER_BLOCK), p.Hkv);
+    page_score_kernel<T, D><<<grid, dim3(256), 0, st>>>(p, qbar, scores, inv_p);
+  }
+}
+
+size_t score_workspace_bytes(const Params& p) {
+  size_t a = (size_t)p.Hq * p.m * p.D * sizeof(float);
+  size_t qb = (size_t)p.Hkv * p.D * sizeof(float);
+  size_t sc = (size_t)p.Hkv * (size_t)(p.n_past > 0 ? p.n_past : 1) * sizeof(float);
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  return up(a) + up(qb) + up(sc);
+}
+
+// Returns hipSuccess or the launch error.  dtype_is_bf16 picks the element type.
+hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel,
+                             int32_t* sel_count, float* scores_out, void* ws, hipStream_t st) {
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  char* w = (char*)ws;
+  float* A = (float*)w;
+  w += up((size_t)p.Hq * p.m * p.D * sizeof(float));
+  float* qbar = (float*)w;
+  w += up((size_t)p.Hkv * p.D * sizeof(float));
+  float* scores = scores_out ? scores_out : (float*)w;
+
+  if (is_bf16) {
+    if (p.D == 128) launch_scoring<bf16_t, 128>(p, A, qbar, scores, st);
+    else launch_scoring<bf16_t, 64>(p, A, qbar, scores, st);
+  } else {
+    if (p.D == 128) launch_scoring<float, 128>(p, A, qbar, scores, st);
+    else launch_scoring<float, 64>(p, A, qbar, scores, st);
+  }
+  static int lds_cap_bytes = 0;
+  constexpr int WANT = 144 * 1024;
+  if (!lds_cap_bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, WANT);
+    lds_cap_bytes = (e == hipSuccess) ? WANT : 48 * 1024;
+    (void)hipGetLastError();
+  }
+  const int64_t cap = lds_cap_bytes / 4;
+  const int64_t cached = p.n_past < cap ? p.n_past : cap;
+  topk_select_kernel<<<dim3(p.Hkv), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
+      scores, p.n_past, p.m, top_k, sel, sel_count, (int32_t)cap);
+  return hipGetLastError();
+}
+
+}  // namespace oomb

@@ -1,0 +1,104 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads,
+exports every symbol the header declares, and rejects bad arguments before any
+launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_02108_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _good_desc(**kw):
+    d = api.AttnDesc(28, 4, 128, 128, 4096, api.BF16, api.F32, 1.0, 65536, 4 * 128 * 128, 128 * 128, 128,
+                     28 * 128, 128, 512)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "oomb.h")).read()
+    declared = set(re.findall(r"\b(oomb_[a-z_]+)\s*\(", header))
+    assert declared == set(api.EXPORTS)
+    l = api.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+    assert api.version() >= 100
+    assert api.status_string(api.OK) == "ok"
+    assert "unsupported" in api.status_string(api.ERR_UNSUPPORTED)
+
+
+def test_descriptor_struct_matches_header_layout():
+    # int32 x7, float, then int64 x7: no padding surprises
+    assert ctypes.sizeof(api.AttnDesc) == 8 * 4 + 7 * 8
+    assert api.AttnDesc.ctx_len.offset == 32
+
+
+def test_workspace_sizes():
+    d = _good_desc()
+    assert api.workspace_bytes(d, 64, api.OP_SCORE_TOPK) >= (28 * 32 * 128 + 4 * 128 + 4 * 480) * 4
+    assert api.workspace_bytes(d, 0, api.OP_ATTN_BWD) >= 28 * 4096 * 4
+    assert api.workspace_bytes(d, 0, api.OP_ATTN_FWD) > 0
+    assert api.workspace_bytes(d, 0, 99) == 0
+    assert api.workspace_bytes(_good_desc(chunk_len=4000), 0, api.OP_ATTN_FWD) == 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(n_kv_heads=5), api.ERR_INVALID_ARG),          # Hq % Hkv != 0
+    (dict(chunk_len=4100), api.ERR_INVALID_ARG),        # C % P != 0
+    (dict(ctx_len=65000), api.ERR_INVALID_ARG),         # N % P != 0
+    (dict(ctx_len=2048), api.ERR_INVALID_ARG),          # N < C
+    (dict(sm_scale=0.0), api.ERR_INVALID_ARG),
+    (dict(dtype=7), api.ERR_INVALID_ARG),
+    (dict(pool_tok_stride=100), api.ERR_INVALID_ARG),   # row shorter than D
+    (dict(q_head_stride=132), api.ERR_INVALID_ARG),     # breaks 16-byte row alignment
+    (dict(num_phys_pages=100), api.ERR_INVALID_ARG),    # fewer physical pages than logical
+    (dict(head_dim=96, pool_tok_stride=96, q_head_stride=96), api.ERR_UNSUPPORTED),
+    (dict(page_size=8, num_phys_pages=8192), api.ERR_UNSUPPORTED),
+])
+def test_bad_descriptors_are_rejected_before_launch(kw, want):
+    d = _good_desc(**kw)
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first
+    l = api.lib()
+    st = l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, 1 << 30, None)
+    assert st == want
+    st = l.oomb_paged_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, fake, fake,
+                               fake, fake, 1 << 30, None)
+    assert st == want
+    st = l.oomb_page_score_topk(ctypes.byref(d), fake, fake, fake, 4, fake, fake, None, fake, 1 << 30, None)
+    assert st == want
+
+
+def test_null_pointers_and_workspace_are_rejected():
+    d = _good_desc()
+    l = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), None, fake, fake, fake, None, None, 0, fake, fake, fake, 256,
+                                 None) == api.ERR_INVALID_ARG
+    assert l.oomb_paged_attn_fwd(None, fake, fake, fake, fake, None, None, 0, fake, fake, fake, 256,
+                                 None) == api.ERR_INVALID_ARG
+    # misaligned tensor pointer
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), ctypes.c_void_p(0x1004), fake, fake, fake, None, None, 0, fake,
+                                 fake, fake, 256, None) == api.ERR_INVALID_ARG
+    # selection list without counts, or a row stride that cannot hold the local pages
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, 96, fake, fake, fake, 256,
+                                 None) == api.ERR_INVALID_ARG
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 8, fake, fake, fake, 256,
+                                 None) == api.ERR_INVALID_ARG
+    # backward / scoring: workspace missing or too small
+    assert l.oomb_paged_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, fake,
+                                 fake, fake, None, 0, None) == api.ERR_WORKSPACE
+    assert l.oomb_paged_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, fake,
+                                 fake, fake, fake, 1024, None) == api.ERR_WORKSPACE
+    assert l.oomb_page_score_topk(ctypes.byref(d), fake, fake, fake, 4, fake, fake, None, fake, 16,
+                                  None) == api.ERR_WORKSPACE
+    assert l.oomb_page_score_topk(ctypes.byref(d), fake, fake, fake, -1, fake, fake, None, fake, 1 << 30,
+                                  None) == api.ERR_INVALID_ARG
+    # more than 2^20 past pages is refused by the selection kernel
+    big = _good_desc(ctx_len=(1 << 21) * 128, num_phys_pages=1 << 21)
+    assert l.oomb_page_score_topk(ctypes.byref(big), fake, fake, fake, 4, fake, fake, None, fake, 1 << 40,
+                                  None) == api.ERR_UNSUPPORTED
