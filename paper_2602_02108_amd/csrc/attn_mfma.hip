@@ -1,11 +1,10 @@
-// bf16 MFMA kernels for gfx950 (P = 128, D = 128).
+// Backward bf16 MFMA kernels (placeholder until they land).
 #include "common.h"
 
 namespace oomb {
-
-bool mfma_supported(const Params& p, bool is_bf16) { (void)p; (void)is_bf16; return false; }
-hipError_t launch_fwd_mfma(const Params&, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_bwd_mfma(const Params&, int32_t, void*, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
+hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void*, hipStream_t st) {
+  return launch_bwd_generic(p, true, max_list_len, st);
+}
 size_t bwd_mfma_workspace_bytes(const Params&, int32_t) { return 0; }
-
 }  // namespace oomb

@@ -76,6 +76,14 @@ WORKLOADS = {
                            extra_phys=5, seed=20260201),
     "tiny_sparse": Workload("tiny_sparse", 2, 1, 64, 16, 128, 1024, 8, "f32", "f32", 0.125,
                             extra_phys=5, boost_frac=0.1, seed=20260201),
+    # small bf16 cases on the MFMA kernels (P = 128, D = 128): Qwen-like GQA 7:1, several row
+    # tiles with a ragged tail
+    "smoke_bf16": Workload("smoke_bf16", 14, 2, 128, 128, 256, 2048, 4, "bf16", "f32", 0.0884,
+                           extra_phys=3, boost_frac=0.2, seed=20260210),
+    "mid_sparse_bf16": Workload("mid_sparse_bf16", 28, 4, 128, 128, 512, 128 * 24, 6, "bf16", "f32",
+                                0.0884, extra_phys=7, boost_frac=0.15, seed=20260211),
+    "mid_dense_bf16": Workload("mid_dense_bf16", 6, 2, 128, 128, 384, 128 * 11, None, "bf16", "bf16",
+                               0.0884, extra_phys=2, seed=20260212),
     # Qwen2.5-7B-shaped layer, dense over a 64K history
     "qwen_dense_64k": _qwen("qwen_dense_64k", 4096, 65536, None, 20260202),
     # sparse, 256K history, 64 retrieved pages

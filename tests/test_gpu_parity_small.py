@@ -92,3 +92,16 @@ def test_backward_is_deterministic():
         outs.append({k: v.clone() for k, v in r.items()})
     for k in outs[0]:
         assert torch.equal(outs[0][k], outs[1][k]), k
+
+
+@pytest.mark.parametrize("name", ["smoke_bf16", "mid_sparse_bf16", "mid_dense_bf16"])
+def test_mfma_bf16(name):
+    rep = pu.full_parity(WORKLOADS[name])
+    _show(name, rep)
+
+
+def test_mfma_bf16_nonzero_pool_and_single_local_page():
+    # chunk of one page, history of three pages, G = 1
+    w = Workload("bf16_g1", 2, 2, 128, 128, 128, 512, 2, "bf16", "f32", 0.0884, seed=31)
+    rep = pu.full_parity(w, init_grad=0.5)
+    _show(w.name, rep)
