@@ -94,9 +94,9 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
     case OOMB_OP_ATTN_FWD:
       return 256;
     case OOMB_OP_ATTN_BWD: {
-      size_t b = up256((size_t)p.Hq * p.C * sizeof(float));
-      if (mfma_supported(p, desc->dtype == OOMB_BF16)) b += bwd_mfma_workspace_bytes(p, (int32_t)p.n);
-      return b;
+      const size_t generic = up256((size_t)p.Hq * p.C * sizeof(float));
+      const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? bwd_mfma_workspace_bytes(p, (int32_t)p.n) : 0;
+      return generic > mfma ? generic : mfma;
     }
     default:
       return 0;
@@ -163,9 +163,7 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
   if (s != OOMB_OK) return s;
   const bool bf = desc->dtype == OOMB_BF16;
   const bool use_mfma = !force_generic() && mfma_supported(p, bf);
-  size_t need = up256((size_t)p.Hq * p.C * sizeof(float));
-  const size_t delta_bytes = need;
-  if (use_mfma) need += bwd_mfma_workspace_bytes(p, max_len);
+  const size_t need = use_mfma ? bwd_mfma_workspace_bytes(p, max_len) : up256((size_t)p.Hq * p.C * sizeof(float));
   if (!workspace || workspace_bytes < need || !aligned16(workspace)) return OOMB_ERR_WORKSPACE;
   p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
   p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
@@ -173,10 +171,14 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
   p.dk_pool = dk_pool; p.dv_pool = dv_pool;
   p.delta = (float*)workspace;
   hipStream_t st = (hipStream_t)hip_stream;
-  hipError_t e = launch_delta(p, bf, st);
-  if (e != hipSuccess) return OOMB_ERR_LAUNCH;
-  if (use_mfma) e = launch_bwd_mfma(p, max_len, (char*)workspace + delta_bytes, st);
-  else e = launch_bwd_generic(p, bf, max_len, st);
+  hipError_t e;
+  if (use_mfma) {
+    e = launch_bwd_mfma(p, max_len, workspace, st);
+  } else {
+    e = launch_delta(p, bf, st);
+    if (e != hipSuccess) return OOMB_ERR_LAUNCH;
+    e = launch_bwd_generic(p, bf, max_len, st);
+  }
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 
