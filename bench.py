@@ -1,0 +1,183 @@
+"""Benchmark of the paged sparse attention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one query chunk of one layer:
+page scoring + top-k selection, paged attention forward, paged attention
+backward (dQ, dK/dV accumulated into the gradient pool).  The default workload
+is the 1M-token-history Qwen2.5-7B-shaped sparse layer; consecutive steps let
+the history grow by one chunk (16 chunks, then it wraps), the gradient pools
+persisting across steps.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def pairs_of(w, N):
+    """Unmasked (query, key) pairs per query head for a chunk ending at N."""
+    n_past = N // w.P - w.m
+    k_eff = n_past if w.top_k is None else min(w.top_k, n_past)
+    return w.C * k_eff * w.P + w.C * (w.C + 1) // 2
+
+
+def cpu_baseline(w, x, sample_tokens):
+    """The CPU oracle, as it stands, on the first `sample_tokens` tokens of the chunk."""
+    import numpy as np
+    import oracle
+    from paper_2602_02108_amd.workloads import to_numpy
+    sub = w.with_(C=sample_tokens, N=w.N - w.C + sample_tokens)
+    sh = oracle.Shape(sub.Hq, sub.Hkv, sub.D, sub.P, sub.C, sub.N, sub.sm_scale)
+    q = to_numpy(x["q"][:sample_tokens])
+    d_o = to_numpy(x["d_o"][:sample_tokens])
+    k_pool, v_pool, pt = to_numpy(x["k_pool"]), to_numpy(x["v_pool"]), to_numpy(x["page_table"])
+    t0 = time.perf_counter()
+    sel = cnt = None
+    if sub.top_k is not None:
+        sel, cnt, _ = oracle.page_score_topk(sh, q, k_pool, pt, sub.top_k)
+    t1 = time.perf_counter()
+    o, lse = oracle.attn_fwd(sh, q, k_pool, v_pool, pt, sel, cnt)
+    dl = oracle.delta(sh, d_o, o)
+    dq = oracle.attn_bwd_dq(sh, q, k_pool, v_pool, pt, lse, dl, d_o, sel, cnt)
+    # dK/dV pools only for the pages the sample touches (the oracle adds in place)
+    dk = np.zeros(k_pool.shape, dtype=np.float32)
+    dv = np.zeros(k_pool.shape, dtype=np.float32)
+    oracle.attn_bwd_dkv(sh, q, k_pool, v_pool, pt, lse, dl, d_o, dk, dv, sel, cnt)
+    t2 = time.perf_counter()
+    flops = 14.0 * sub.D * pairs_of(sub, sub.N) * sub.Hq
+    return {"value": flops / (t2 - t0) / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {sample_tokens} tokens of the chunk, all {sub.Hq} heads, full page scoring "
+                      f"({sub.n_past} pages) + top-{sub.top_k} + fwd + bwd; scoring {t1 - t0:.2f} s, "
+                      f"attention {t2 - t1:.2f} s",
+            "seconds": t2 - t0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="qwen_sparse_1m")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_02108_amd import api
+    from paper_2602_02108_amd.workloads import WORKLOADS, make_inputs, torch_dtype
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    api.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    w = WORKLOADS[args.workload]
+    x = make_inputs(w, dev)
+    grow = w.extra_phys // w.m + 1          # chunks the pre-filled pool can hold
+    gdt = torch_dtype(w.grad_dtype)
+
+    def desc_at(step):
+        N = w.N + (step % grow) * w.C
+        return N, api.make_desc(x["q"], x["k_pool"], N, w.sm_scale, gdt)
+
+    top_k = w.top_k
+    n_max, d_max = desc_at(grow - 1)
+    ws_sc = torch.empty(max(api.workspace_bytes(d_max, top_k or 0, api.OP_SCORE_TOPK), 256), dtype=torch.uint8, device=dev)
+    ws_fw = torch.empty(api.workspace_bytes(d_max, 0, api.OP_ATTN_FWD), dtype=torch.uint8, device=dev)
+    ws_bw = torch.empty(api.workspace_bytes(d_max, 0, api.OP_ATTN_BWD), dtype=torch.uint8, device=dev)
+    sel = torch.empty((w.Hkv, (top_k or 0) + w.m), dtype=torch.int32, device=dev)
+    cnt = torch.empty((w.Hkv,), dtype=torch.int32, device=dev)
+    o = torch.empty_like(x["q"])
+    lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(x["q"])
+
+    def step(s):
+        N, desc = desc_at(s)
+        if top_k is not None:
+            api.page_score_topk(desc, x["q"], x["k_pool"], x["page_table"], top_k, sel, cnt, workspace=ws_sc)
+            sl, ct = sel, cnt
+        else:
+            sl = ct = None
+        api.paged_attn_fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sl, ct, o, lse, ws_fw)
+        api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"],
+                           x["dk_pool"], x["dv_pool"], sl, ct, dq, ws_bw)
+        return N
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    api.profile_reset()
+    api.profile_enable(True)
+    flops = 0.0
+    kv_bytes = 0.0
+    pairs_sum = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        N = step(s)
+        pr = pairs_of(w, N)
+        pairs_sum += pr
+        flops += 14.0 * w.D * pr * w.Hq
+        n_past = N // w.P - w.m
+        k_eff = n_past if top_k is None else min(top_k, n_past)
+        page_bytes = w.P * w.D * 2 * w.Hkv
+        grad_bytes = w.P * w.D * (2 if w.grad_dtype == "bf16" else 4) * w.Hkv
+        scored = n_past * page_bytes if top_k is not None else 0
+        # K scored once + K,V gathered by forward + dK,dV pages read and written by backward
+        kv_bytes += scored + 2 * (k_eff + w.m) * page_bytes + 2 * 2 * (k_eff + w.m) * grad_bytes
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    api.profile_enable(False)
+    prof = api.profile_read()
+    dt = t1 - t0
+
+    # dominant kernel and its roofline
+    name, (ms_tot, launches) = max(prof.items(), key=lambda kv: kv[1][0])
+    avg_ms = ms_tot / max(launches, 1)
+    pairs_avg = pairs_sum / args.steps
+    credited = {"attn_fwd_mfma": 4.0, "bwd_dq_mfma": 6.0, "bwd_dkv_mfma": 4.0}  # x D x pairs x Hq, algorithmic
+    if name in credited:
+        ach = credited[name] * w.D * pairs_avg * w.Hq / (avg_ms * 1e-3) / 1e12
+        roof = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": avg_ms, "launches": launches}
+    else:
+        n_past = w.n_past
+        by = n_past * w.P * w.D * 2 * w.Hkv
+        ach = by / (avg_ms * 1e-3) / 1e9
+        roof = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_ms": avg_ms, "launches": launches}
+    kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof.items()}
+    if "page_score" in kernels:
+        by = sum((desc_at(s)[0] // w.P - w.m) for s in range(args.steps)) / args.steps * w.P * w.D * 2 * w.Hkv
+        kernels["page_score"]["GB/s"] = by / (kernels["page_score"]["avg_ms"] * 1e-3) / 1e9
+        kernels["page_score"]["frac_hbm_peak"] = kernels["page_score"]["GB/s"] / HBM_PEAK_GBS
+
+    out = {
+        "metric": "paged sparse attn fwd+bwd TFLOP/s and KV GB/s per layer at 1M-token history",
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.D, "page_size": w.P,
+                   "chunk": w.C, "history_tokens_first_step": w.N, "history_growth_per_step": w.C,
+                   "top_k_pages": w.top_k, "local_pages": w.m, "grad_pool_dtype": w.grad_dtype},
+        "kv_gbps": kv_bytes / dt / 1e9,
+        "frac_mfma_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "kernels": kernels,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -141,6 +141,21 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
                                 const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Benchmark aid (not part of the paper's method): per-kernel device time.  While
+ * enabled, every kernel the library launches is bracketed by two HIP events
+ * recorded on the caller's stream (events are host objects created on demand; no
+ * device memory is allocated).  oomb_profile_read waits for the recorded events of
+ * entry idx (0 <= idx < oomb_profile_count()) and returns the kernel's name, its
+ * accumulated device time in milliseconds and its launch count; it returns
+ * OOMB_ERR_INVALID_ARG for a bad index or NULL outputs.  oomb_profile_reset drops
+ * all entries.  Not thread-safe against concurrent launches on other threads.
+ */
+void oomb_profile_enable(int32_t on);
+void oomb_profile_reset(void);
+int32_t oomb_profile_count(void);
+int32_t oomb_profile_read(int32_t idx, char* name, int32_t name_cap, double* total_ms, int64_t* launches);
+
 const char* oomb_status_string(int32_t status);
 
 /* major * 10000 + minor * 100 + patch */

@@ -86,6 +86,11 @@ def _lib(prec: str):
     return _libs[prec]
 
 
+def num_threads() -> int:
+    """Threads the OpenMP loops of the attention functions use."""
+    return int(_lib("f32").oomb_oracle_num_threads())
+
+
 def _real(prec: str):
     return np.float32 if prec == "f32" else np.float64
 

@@ -72,6 +72,13 @@ typedef struct {
 
 int oomb_oracle_real_bytes(void) { return (int)sizeof(real); }
 
+#ifdef _OPENMP
+#include <omp.h>
+int oomb_oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oomb_oracle_num_threads(void) { return 1; }
+#endif
+
 static inline real ld(const void *base, int64_t idx, int is_bf16) {
   if (is_bf16) {
     uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;

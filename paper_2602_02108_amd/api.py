@@ -17,7 +17,8 @@ F32, BF16 = 0, 1
 OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD = 0, 1, 2
 
 EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
-           "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version"]
+           "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
+           "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -62,6 +63,13 @@ def lib():
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
+        l.oomb_profile_enable.restype = None
+        l.oomb_profile_enable.argtypes = [i32]
+        l.oomb_profile_reset.restype = None
+        l.oomb_profile_count.restype = i32
+        l.oomb_profile_read.restype = i32
+        l.oomb_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_int64)]
         _lib = l
     return _lib
 
@@ -160,3 +168,26 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
     if st != OK:
         raise OombError(st, "oomb_paged_attn_bwd")
     return d_q
+
+
+def profile_enable(on: bool) -> None:
+    """oomb_profile_enable: bracket every kernel launch with HIP events on the launch stream."""
+    lib().oomb_profile_enable(1 if on else 0)
+
+
+def profile_reset() -> None:
+    lib().oomb_profile_reset()
+
+
+def profile_read() -> dict:
+    """oomb_profile_read for every entry: {kernel name: (total_ms, launches)}."""
+    out = {}
+    for idx in range(lib().oomb_profile_count()):
+        name = ctypes.create_string_buffer(64)
+        ms = ctypes.c_double()
+        n = ctypes.c_int64()
+        st = lib().oomb_profile_read(idx, name, 64, ctypes.byref(ms), ctypes.byref(n))
+        if st != OK:
+            raise OombError(st, "oomb_profile_read")
+        out[name.value.decode()] = (ms.value, n.value)
+    return out

@@ -66,6 +66,8 @@ oomb_status check_desc(const oomb_attn_desc* d, Params* p) {
   p->pool_tok_stride = d->pool_tok_stride;
   p->q_tok_stride = d->q_tok_stride; p->q_head_stride = d->q_head_stride;
   p->grad_is_bf16 = d->grad_dtype == OOMB_BF16;
+  p->g_magic = p->G > 1 ? (uint32_t)(((1ull << 32) + (uint64_t)p->G - 1) / (uint64_t)p->G) : 0u;
+  if ((int64_t)p->C * p->G >= (1ll << 31) / p->G) return OOMB_ERR_UNSUPPORTED;
   return OOMB_OK;
 }
 

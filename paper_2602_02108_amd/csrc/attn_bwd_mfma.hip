@@ -126,7 +126,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
                                                             int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, lq = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hh = lane >> 5, lq = lane & 31;
   int g, tile;
   if (xcd_map) {
     const int xcd = blockIdx.x & 7, per = 8 / p.Hkv;
@@ -263,16 +263,18 @@ struct KvStage {
   uint4 qn[2], don[2];
   uint32_t qt[8], dot[8];
   // 64 rows of row space starting at R0
-  __device__ __forceinline__ void load(const Params& p, int g, int64_t R0, int64_t rows_total, int tid, int wave,
+  __device__ __forceinline__ void load(const Params& p, int g, uint32_t R0, uint32_t rows_total, int tid, int wave,
                                        int lane) {
     const bf16_t* q = (const bf16_t*)p.q;
     const bf16_t* d_o = (const bf16_t*)p.d_o;
+    const int64_t hbase = (int64_t)g * p.G * p.q_head_stride;
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
       const int gi = tid + BW_THREADS * x;
-      const int64_t rr = R0 + (gi >> 4);
+      const uint32_t rr = R0 + (gi >> 4);
       if (rr < rows_total) {
-        const int64_t o = (rr / p.G) * p.q_tok_stride + (g * p.G + rr % p.G) * p.q_head_stride + (gi & 15) * 8;
+        const uint32_t i = div_g(p, rr), hd = rr - i * p.G;
+        const int64_t o = (int64_t)i * p.q_tok_stride + hbase + (int64_t)hd * p.q_head_stride + (gi & 15) * 8;
         qn[x] = *reinterpret_cast<const uint4*>(q + o);
         don[x] = *reinterpret_cast<const uint4*>(d_o + o);
       } else {
@@ -283,9 +285,10 @@ struct KvStage {
     const int u = wave >> 1, h2 = wave & 1;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int64_t rr = R0 + 16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2);
+      const uint32_t rr = R0 + 16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2);  // wave-uniform
       if (rr < rows_total) {
-        const int64_t o = (rr / p.G) * p.q_tok_stride + (g * p.G + rr % p.G) * p.q_head_stride + 2 * lane;
+        const uint32_t i = div_g(p, rr), hd = rr - i * p.G;
+        const int64_t o = (int64_t)i * p.q_tok_stride + hbase + (int64_t)hd * p.q_head_stride + 2 * lane;
         qt[e] = *reinterpret_cast<const uint32_t*>(q + o);
         dot[e] = *reinterpret_cast<const uint32_t*>(d_o + o);
       } else {
@@ -330,7 +333,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dkv_kernel(Params p, const flo
                                                              const float* __restrict__ lse2_rs, int64_t rows_pad,
                                                              int32_t max_len, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, lq = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hh = lane >> 5, lq = lane & 31;
   const int kbw = wave & 3, qh = wave >> 2;
   int g;
   int32_t j;
@@ -380,7 +383,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dkv_kernel(Params p, const flo
 
   KvStage stg;
   if (s0 < s_end) {
-    stg.load(p, g, s0 * 64, rows_total, tid, wave, lane);
+    stg.load(p, g, (uint32_t)(s0 * 64), (uint32_t)rows_total, tid, wave, lane);
     stg.store(stages, tid, wave, lane);
   }
   __syncthreads();
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dkv_kernel(Params p, const flo
   for (int64_t s = s0; s < s_end; ++s) {
     const int b = (int)((s - s0) & 1);
     const unsigned char* sb = stages + b * KV_STAGE;
-    if (s + 1 < s_end) stg.load(p, g, (s + 1) * 64, rows_total, tid, wave, lane);
+    if (s + 1 < s_end) stg.load(p, g, (uint32_t)((s + 1) * 64), (uint32_t)rows_total, tid, wave, lane);
 
     const int64_t R0 = s * 64 + 32 * qh;  // first row of this wave's 32-query block
     f32x16 sc, dp;
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dkv_kernel(Params p, const flo
       sc = mfma32(lds_frag<16>(sb, 32 * qh + lq, 2 * kk + hh), kf[kk], sc);
       dp = mfma32(lds_frag<16>(sb + 16384, 32 * qh + lq, 2 * kk + hh), lds_frag<16>(vt, 32 * kbw + lq, 2 * kk + hh), dp);
     }
-    const bool diag = first_q + R0 / p.G < first + TP - 1;  // some (row, key) of the block may be masked
+    const bool diag = first_q + div_g(p, (uint32_t)R0) < first + TP - 1;  // some (row, key) of the block may be masked
     const float* l2p = lse2_rs + (int64_t)g * rows_pad + R0 + 4 * hh;
     const float* dlp = delta_rs + (int64_t)g * rows_pad + R0 + 4 * hh;
 #pragma unroll
@@ -414,7 +417,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dkv_kernel(Params p, const flo
         float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[x], c, -l2v[bb]));
         if (diag) {
           const int64_t row = R0 + 8 * a + 4 * hh + bb;
-          if (key_pos > first_q + row / p.G) pr = 0.f;
+          if (key_pos > first_q + div_g(p, (uint32_t)row)) pr = 0.f;
         }
         sc[x] = pr;
         dp[x] = pr * (dp[x] - dlv[bb]);
@@ -487,6 +490,7 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   float* lse2_rs = delta_rs + (size_t)p.Hkv * rows_pad;
   {
     const int64_t total = (int64_t)p.Hkv * rows_pad;
+    ProfScope prof_("bwd_prep", st);
     bwd_prep_kernel<<<dim3((unsigned)((total + 15) / 16)), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad);
   }
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
@@ -494,10 +498,12 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   {
     const int tiles = (int)(((int64_t)p.C * p.G + DQ_ROWS - 1) / DQ_ROWS);
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
+    ProfScope prof_("bwd_dq_mfma", st);
     bwd_dq_kernel<<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
   }
   {
     const unsigned blocks = xcd_map ? 8u * (unsigned)((max_list_len + per - 1) / per) : (unsigned)max_list_len * p.Hkv;
+    ProfScope prof_("bwd_dkv_mfma", st);
     if (p.grad_is_bf16)
       bwd_dkv_kernel<bf16_t><<<dim3(blocks), dim3(BW_THREADS), KV_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, max_list_len, xcd_map);
     else

@@ -6,10 +6,18 @@
 // token by token, so the K/V tiles staged in LDS are shared by all query heads
 // of the group and a workgroup's rows span only 256 / G tokens (short causal
 // diagonal).  Each wave keeps its 32 query rows (as the B operand of
-// S^T = K Q^T) and its 32 x 128 output block in registers; K is staged as a
-// natural tile, V as a transposed tile (see mfma_common.h), double buffered.
-// In the S^T layout every lane owns one query row, so the online-softmax
+// S^T = K Q^T) and its 32 x 128 output block in registers.  Pages are processed
+// as two half tiles of 64 keys: K as a natural half tile (direct global -> LDS
+// loads, double buffered), V as a transposed half tile (triple buffered).  In
+// the S^T layout every lane owns one query row, so the online-softmax
 // statistics are per-lane scalars.
+//
+// Schedule (one barrier per half tile t): S_t = K_t Q^T, online softmax, then
+// O += V_t P_t.  LDS operand fragments are fetched in batches of four, one batch
+// ahead of the matrix instructions that use them.  The two waves that share a
+// SIMD (w and w + 4) place the O += V P product at opposite ends of the
+// iteration (waves 0-3 right after their softmax, waves 4-7 at the top of the
+// next iteration), so one wave's matrix work overlaps the other wave's vector work.
 #include "mfma_common.h"
 
 namespace oomb {
@@ -17,11 +25,15 @@ namespace oomb {
 constexpr int FW_WAVES = 8;
 constexpr int FW_THREADS = FW_WAVES * 64;
 constexpr int FW_ROWS = FW_WAVES * 32;
-constexpr int FW_LDS = 4 * TILE_BYTES;  // K0 K1 V0 V1
+constexpr int HT = 64;                    // keys per half tile
+constexpr int HT_BYTES = HT * HD * 2;     // 16 KiB
+constexpr int FW_LDS = 5 * HT_BYTES;      // K0 K1 V0 V1 V2
 
 __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, lq = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;  // waves w and w + 4 share a SIMD
 
   // workgroup -> (KV head, row tile).  Workgroups are dealt round-robin to the 8
   // XCDs; keeping a KV head on a fixed set of XCDs lets its pages stay in that L2.
@@ -37,148 +49,260 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   if (tile >= tiles_per_head) return;
   tile = tiles_per_head - 1 - tile;  // rows late in the chunk see more local pages: start them first
 
-  const int64_t rows_total = (int64_t)p.C * p.G;
-  const int64_t row0 = (int64_t)tile * FW_ROWS;
+  const uint32_t rows_total = (uint32_t)p.C * p.G;
+  const uint32_t row0 = (uint32_t)tile * FW_ROWS;
   const int64_t first_q = p.N - p.C;
 
   // this lane's query row
-  const int64_t r_raw = row0 + wave * 32 + lq;
+  const uint32_t r_raw = row0 + wave * 32 + lq;
   const bool r_valid = r_raw < rows_total;
-  const int64_t r = r_valid ? r_raw : rows_total - 1;
-  const int i = (int)(r / p.G), h = g * p.G + (int)(r % p.G);
+  const uint32_t r = r_valid ? r_raw : rows_total - 1;
+  const uint32_t i = div_g(p, r);
+  const int h = g * p.G + (int)(r - i * p.G);
   const int64_t a_i = first_q + i;
   // wave-uniform bounds of the wave's rows (for skipping / masking decisions)
-  const int64_t rw_lo = row0 + wave * 32, rw_hi_raw = rw_lo + 31;
-  const int64_t rw_hi = rw_hi_raw < rows_total ? rw_hi_raw : rows_total - 1;
-  const int64_t a_wave_min = first_q + (rw_lo < rows_total ? rw_lo : rows_total - 1) / p.G;
-  const int64_t a_wave_max = first_q + rw_hi / p.G;
-  const int64_t rb_hi = (row0 + FW_ROWS - 1 < rows_total) ? row0 + FW_ROWS - 1 : rows_total - 1;
-  const int64_t a_blk_max = first_q + rb_hi / p.G;
+  const uint32_t rw_lo = row0 + wave * 32;
+  const uint32_t rw_hi = (rw_lo + 31 < rows_total) ? rw_lo + 31 : rows_total - 1;
+  const int64_t a_wave_min = first_q + div_g(p, rw_lo < rows_total ? rw_lo : rows_total - 1);
+  const int64_t a_wave_max = first_q + div_g(p, rw_hi);
+  const uint32_t rb_hi = (row0 + FW_ROWS - 1 < rows_total) ? row0 + FW_ROWS - 1 : rows_total - 1;
+  const int64_t a_blk_max = first_q + div_g(p, rb_hi);
 
-  // number of list entries visible to this workgroup (lists are ascending)
-  int32_t T = list_len(p, g);
-  {
-    const int64_t l_max = a_blk_max / TP;
-    while (T > 0 && list_at(p, g, T - 1) > l_max) --T;
-  }
+  // number of half tiles visible to this workgroup (lists are ascending)
+  const int32_t T = visible_len(p, g, a_blk_max / TP, lane);
+  PageWindow pw;
+  pw.init(p, g, T, lane);
+  int32_t T2 = 2 * T;
+  if (T > 0 && (int64_t)list_at(p, g, T - 1) * TP + HT > a_blk_max) T2 -= 1;  // second half of the last page unseen
 
   const bf16_t* qrow = (const bf16_t*)p.q + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
   bf16x8 qf[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + 16 * kk + 8 * hh));
 
-  f32x16 of[4];
+  f32x16 of[4], sc[2];
+  bf16x8 pf[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int x = 0; x < 16; ++x) of[db][x] = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) pf[u] = as_bf16x8(make_uint4(0, 0, 0, 0));
   float m_run = -1e30f, l_run = 0.f;
   const float c = p.sm_scale * 1.4426950408889634f;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-  NaturalStage<FW_THREADS> ks;
-  TransposedStage<FW_WAVES> vs;
-  auto tile_ptrs = [&](int32_t j, const bf16_t*& kb, const bf16_t*& vb, int64_t& first) {
-    const int64_t l = list_at(p, g, j);
-    const int64_t off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
-    kb = (const bf16_t*)p.k_pool + off;
-    vb = (const bf16_t*)p.v_pool + off;
-    first = l * TP;
-  };
-
-  const bf16_t *kb, *vb;
-  int64_t first = 0, first_next = 0;
-  if (T > 0) {
-    tile_ptrs(0, kb, vb, first);
-    ks.load(kb, p.pool_tok_stride, tid);
-    vs.load(vb, p.pool_tok_stride, wave, lane);
-    ks.store(smem, tid);
-    vs.store(smem + 2 * TILE_BYTES, wave, lane);
+  // LDS operand addresses.  The swizzles XOR a per-lane constant into the granule
+  // index, so an operand address is (lane base ^ small constant) + block offset; the
+  // block offset goes into the instruction's immediate field.
+  uint32_t ka[8], va[4];
+  {
+    const uint32_t kbase = lq * 256 + (((lq & 15) ^ hh) << 4);           // natural, 16 granules per row
+    const uint32_t vbase = lq * 128 + ((((lq >> 1) & 7) ^ hh) << 4);     // transposed, 8 granules per row
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ka[j] = kbase ^ (j << 5);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) va[j] = vbase ^ (j << 5);
   }
-  __syncthreads();
+  unsigned char* const kbuf = smem;
+  unsigned char* const vbuf = smem + 2 * HT_BYTES;
 
-  for (int32_t j = 0; j < T; ++j) {
-    const int b = j & 1;
-    const unsigned char* kt = smem + b * TILE_BYTES;
-    const unsigned char* vt = smem + (2 + b) * TILE_BYTES;
-    const bool more = j + 1 < T;
-    if (more) {
-      tile_ptrs(j + 1, kb, vb, first_next);
-      ks.load(kb, p.pool_tok_stride, tid);
-      vs.load(vb, p.pool_tok_stride, wave, lane);
+  // half tile ht: page j = ht / 2, keys 64 (ht % 2) .. + 63 of it
+  auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * HT; };
+  auto ht_off = [&](int32_t ht) -> int64_t {
+    return (int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
+           (int64_t)(ht & 1) * HT * p.pool_tok_stride;
+  };
+  // this wave's share of a K half tile: 8 rows, two 1 KiB chunks, straight into LDS
+  auto load_k = [&](int32_t ht, unsigned char* dst) {
+    const bf16_t* base = (const bf16_t*)p.k_pool + ht_off(ht) + (int64_t)(8 * wave) * p.pool_tok_stride;
+    const uint32_t ts_bytes = (uint32_t)p.pool_tok_stride * 2u;
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const uint32_t lrow = 4 * x + (lane >> 4);
+      const uint32_t cc = (lane & 15) ^ ((8 * wave + lrow) & 15);
+      const char* src = reinterpret_cast<const char*>(base) + (lrow * ts_bytes + cc * 16u);
+      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(dst + (8 * wave + 4 * x) * 256), 16, 0, 0);
     }
-
-    if (first <= a_wave_max) {  // wave-uniform: some row of this wave sees the tile
-      // S^T = K Q^T : 4 key blocks of 32, contraction over the head dim in 8 steps
-      f32x16 s[4];
+  };
+  // this wave's octet (index = wave) of a V half tile: tokens 16u + 4h2 + {0..3, 8..11}
+  uint32_t vr[8];
+  auto load_v = [&](int32_t ht) {
+    const bf16_t* base = (const bf16_t*)p.v_pool + ht_off(ht);
+    const int u = wave >> 1, h2 = wave & 1;
 #pragma unroll
-      for (int kbk = 0; kbk < 4; ++kbk) {
+    for (int e = 0; e < 8; ++e) {
+      const int tok = 16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2);
+      vr[e] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(base + (int64_t)tok * p.pool_tok_stride) +
+                                                 (uint32_t)lane * 4u);
+    }
+  };
+  auto store_v = [&](unsigned char* dst) {
+    uint4 lo, hi;
+    lo.x = __builtin_amdgcn_perm(vr[1], vr[0], 0x05040100u);
+    lo.y = __builtin_amdgcn_perm(vr[3], vr[2], 0x05040100u);
+    lo.z = __builtin_amdgcn_perm(vr[5], vr[4], 0x05040100u);
+    lo.w = __builtin_amdgcn_perm(vr[7], vr[6], 0x05040100u);
+    hi.x = __builtin_amdgcn_perm(vr[1], vr[0], 0x07060302u);
+    hi.y = __builtin_amdgcn_perm(vr[3], vr[2], 0x07060302u);
+    hi.z = __builtin_amdgcn_perm(vr[5], vr[4], 0x07060302u);
+    hi.w = __builtin_amdgcn_perm(vr[7], vr[6], 0x07060302u);
+    const int d0 = 2 * lane, d1 = 2 * lane + 1;
+    *reinterpret_cast<uint4*>(dst + (d0 * 8 + (wave ^ ((d0 >> 1) & 7))) * 16) = lo;
+    *reinterpret_cast<uint4*>(dst + (d1 * 8 + (wave ^ ((d1 >> 1) & 7))) * 16) = hi;
+  };
+  // S^T (64 keys x 32 queries) = K Q^T; fragments fetched one batch of four ahead
+  auto qk = [&](f32x16* dst, const unsigned char* kt) {
+    uint4 fa[4], fb[4];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) s[kbk][x] = 0.f;
+    for (int j = 0; j < 4; ++j) fa[j] = *reinterpret_cast<const uint4*>(kt + ka[j]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-          s[kbk] = mfma32(as_bf16x8(lds_read16(kt, 32 * kbk + lq, 2 * kk + hh)), qf[kk], s[kbk]);
-      }
-      if (first + TP - 1 > a_wave_min) {  // diagonal tile: mask keys after the query
+    for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const uint4*>(kt + ka[4 + j]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kbk = 0; kbk < 4; ++kbk)
+    for (int x = 0; x < 16; ++x) { dst[0][x] = 0.f; dst[1][x] = 0.f; }
 #pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            const int64_t key = first + 32 * kbk + 8 * (x >> 2) + 4 * hh + (x & 3);
-            if (key > a_i) s[kbk][x] = -INFINITY;
-          }
-      }
-      float mx = s[0][0];
+    for (int j = 0; j < 4; ++j) dst[0] = mfma32(as_bf16x8(fa[j]), qf[j], dst[0]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kbk = 0; kbk < 4; ++kbk)
+    for (int j = 0; j < 4; ++j) fa[j] = *reinterpret_cast<const uint4*>(kt + ka[j] + 8192);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s[kbk][x]);
-      mx = half_max(mx);
-      const float m_new = fmaxf(m_run, mx);
-      const float mc = m_new * c;
-      float rs = 0.f;
-      bf16x8 pf[8];
+    for (int j = 0; j < 4; ++j) dst[0] = mfma32(as_bf16x8(fb[j]), qf[4 + j], dst[0]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kbk = 0; kbk < 4; ++kbk) {
+    for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const uint4*>(kt + ka[4 + j] + 8192);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          s[kbk][x] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kbk][x], c, -mc));
-          rs += s[kbk][x];
-        }
+    for (int j = 0; j < 4; ++j) dst[1] = mfma32(as_bf16x8(fa[j]), qf[j], dst[1]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          uint4 w;
-          w.x = pack2_bf16(s[kbk][8 * u + 0], s[kbk][8 * u + 1]);
-          w.y = pack2_bf16(s[kbk][8 * u + 2], s[kbk][8 * u + 3]);
-          w.z = pack2_bf16(s[kbk][8 * u + 4], s[kbk][8 * u + 5]);
-          w.w = pack2_bf16(s[kbk][8 * u + 6], s[kbk][8 * u + 7]);
-          pf[2 * kbk + u] = as_bf16x8(w);
-        }
-      }
-      if (__any(m_new != m_run)) {  // wave-uniform: rescale only when some row's maximum moved
-        const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(m_run, c, -mc));
-        l_run *= alpha;
+    for (int j = 0; j < 4; ++j) dst[1] = mfma32(as_bf16x8(fb[j]), qf[4 + j], dst[1]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // O^T (128 dims x 32 queries) += V^T P^T
+  auto pv = [&](const unsigned char* vt) {
+    uint4 fa[4], fb[4];
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+    for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(vt + va[u]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int x = 0; x < 16; ++x) of[db][x] *= alpha;
-        m_run = m_new;
-      }
-      l_run += rs;
-      // O^T += V^T P^T : 4 head-dim blocks of 32, contraction over 8 groups of 16 keys
+    for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 4096);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) of[0] = mfma32(as_bf16x8(fa[u]), pf[u], of[0]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 2 * 4096);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) of[1] = mfma32(as_bf16x8(fb[u]), pf[u], of[1]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 3 * 4096);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) of[2] = mfma32(as_bf16x8(fa[u]), pf[u], of[2]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) of[3] = mfma32(as_bf16x8(fb[u]), pf[u], of[3]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // causal mask of a diagonal half tile (first token `first`) + row maximum, merged with
+  // the running maximum.  Done as soon as a half tile's S is complete, one iteration
+  // before its exponentials, so that the exponentials never wait for a reduction.
+  auto mask_and_max = [&](f32x16* sv, int64_t first) -> float {
+    if (first + HT - 1 > a_wave_min) {
+      const int rel = (int)(a_i - first) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+        for (int x = 0; x < 16; ++x)
+          if (32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) sv[kb2][x] = -INFINITY;
+    }
+    float mx = sv[0][0];
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+      for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sv[kb2][x]);
+    return half_max(mx);
+  };
+  // m_run <- max(m_run, m_tile); O and l are rescaled only when some row's maximum moved
+  auto rescale = [&](float m_tile) {
+    const float m_new = fmaxf(m_run, m_tile);
+    if (__any(m_new != m_run)) {  // wave-uniform
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-          of[db] = mfma32(as_bf16x8(lds_read16(vt, 32 * db + lq, 2 * u + hh)), pf[u], of[db]);
+        for (int x = 0; x < 16; ++x) of[db][x] *= alpha;
+      m_run = m_new;
     }
+  };
+  // P = exp2(c S - c m_run) of the half tile in sc, rounded to bf16 into pf; returns the
+  // row sum of the rounded probabilities (what the PV product uses)
+  auto exps = [&]() -> float {
+    const float mc = m_run * c;
+    float rs = 0.f;
+#pragma unroll
+    for (int kb2 = 0; kb2 < 2; ++kb2) {
+#pragma unroll
+      for (int x = 0; x < 16; ++x) sc[kb2][x] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb2][x], c, -mc));
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint4 w;
+        w.x = pack2_bf16(sc[kb2][8 * u + 0], sc[kb2][8 * u + 1]);
+        w.y = pack2_bf16(sc[kb2][8 * u + 2], sc[kb2][8 * u + 3]);
+        w.z = pack2_bf16(sc[kb2][8 * u + 4], sc[kb2][8 * u + 5]);
+        w.w = pack2_bf16(sc[kb2][8 * u + 6], sc[kb2][8 * u + 7]);
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), ones, rs, false);
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), ones, rs, false);
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), ones, rs, false);
+        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), ones, rs, false);
+        pf[2 * kb2 + u] = as_bf16x8(w);
+      }
+    }
+    return rs;
+  };
 
+  // prologue: K_0 and V_0 into LDS
+  if (T2 > 0) {
+    load_k(0, kbuf);
+    load_v(0);
+    store_v(vbuf);
+  }
+  wait_vmem();
+  __syncthreads();
+  bool act_prev = false;  // did this wave compute P for half tile t - 1
+
+  for (int32_t t = 0; t < T2; ++t) {
+    pw.advance(p, g, T, t >> 1, lane);
+    // tiles for the next iteration: K_{t+1} into the other K buffer, V_{t+1} into the third V buffer
+    const bool more = t + 1 < T2;
     if (more) {
-      ks.store(smem + (b ^ 1) * TILE_BYTES, tid);
-      vs.store(smem + (2 + (b ^ 1)) * TILE_BYTES, wave, lane);
-      first = first_next;
+      load_k(t + 1, kbuf + ((t + 1) & 1) * HT_BYTES);
+      load_v(t + 1);
     }
+    if (grp == 1 && act_prev) pv(vbuf + ((t + 2) % 3) * HT_BYTES);  // waves 4-7: product of half tile t - 1
+
+    const int64_t first = ht_first(t);
+    const bool act = first <= a_wave_max;  // some row of this wave sees the half tile
+    if (act) {
+      qk(sc, kbuf + (t & 1) * HT_BYTES);
+      const float m_tile = mask_and_max(sc, first);
+      rescale(m_tile);
+      l_run += exps();
+      if (grp == 0) pv(vbuf + (t % 3) * HT_BYTES);  // waves 0-3: product of this half tile
+    }
+    act_prev = act;
+
+    if (more) store_v(vbuf + ((t + 1) % 3) * HT_BYTES);
+    wait_vmem();
     __syncthreads();
   }
+  if (grp == 1 && act_prev) pv(vbuf + ((T2 - 1) % 3) * HT_BYTES);
 
   // epilogue: O = acc / l, LSE = ln(2) * (m * c + log2 l)
   const float l_tot = half_sum(l_run);
@@ -219,7 +343,7 @@ hipError_t launch_fwd_mfma(const Params& p, hipStream_t st) {
   } else {
     blocks = (unsigned)tiles * p.Hkv;
   }
-  fwd_mfma_kernel<<<dim3(blocks), dim3(FW_THREADS), FW_LDS, st>>>(p, tiles, xcd_map);
+  { ProfScope prof_("attn_fwd_mfma", st); fwd_mfma_kernel<<<dim3(blocks), dim3(FW_THREADS), FW_LDS, st>>>(p, tiles, xcd_map); }
   return hipGetLastError();
 }
 

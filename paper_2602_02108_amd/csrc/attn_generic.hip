@@ -242,6 +242,7 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void dkv_generic_kernel(Params p) {
 hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st) {
   const int64_t rows = (int64_t)p.C * p.Hq;
   dim3 grid((unsigned)((rows + 3) / 4));
+  ProfScope prof_("delta", st);
   if (is_bf16) delta_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(p);
   else delta_kernel<float><<<grid, dim3(256), 0, st>>>(p);
   return hipGetLastError();
@@ -250,6 +251,7 @@ hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st) {
 hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st) {
   const int64_t rows = (int64_t)p.C * p.Hq;
   dim3 grid((unsigned)((rows + GEN_WAVES - 1) / GEN_WAVES));
+  ProfScope prof_("attn_fwd_generic", st);
   if (is_bf16) fwd_generic_kernel<bf16_t><<<grid, dim3(64 * GEN_WAVES), 0, st>>>(p);
   else fwd_generic_kernel<float><<<grid, dim3(64 * GEN_WAVES), 0, st>>>(p);
   return hipGetLastError();
@@ -261,6 +263,7 @@ hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_le
   dim3 grid((unsigned)((rows + GEN_WAVES - 1) / GEN_WAVES));
   dim3 gkv((unsigned)((p.P + GEN_WAVES - 1) / GEN_WAVES), (unsigned)max_list_len, (unsigned)p.Hkv);
   dim3 blk(64 * GEN_WAVES);
+  ProfScope prof_("attn_bwd_generic", st);
   if (is_bf16) {
     dq_generic_kernel<bf16_t><<<grid, blk, 0, st>>>(p);
     if (p.grad_is_bf16) dkv_generic_kernel<bf16_t, bf16_t><<<gkv, blk, 0, st>>>(p);

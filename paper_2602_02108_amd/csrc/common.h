@@ -29,6 +29,7 @@ struct Params {
   void* dv_pool;
   float* delta;              // [Hq][C], workspace
   int32_t grad_is_bf16;
+  uint32_t g_magic;          // ceil(2^32 / G): row / G == umulhi(row, g_magic) for row < 2^32 / G, G > 1
 };
 
 typedef uint16_t bf16_t;  // raw bit pattern
@@ -53,6 +54,23 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
   static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
+
+// Brackets a kernel launch with HIP events when benchmark profiling is enabled
+// (oomb_profile_enable); does nothing otherwise.
+class ProfScope {
+ public:
+  ProfScope(const char* name, hipStream_t st);
+  ~ProfScope();
+ private:
+  hipStream_t stream_;
+  int slot_;
+  hipEvent_t start_;
+};
+
+// row-space index -> chunk token (row / G) without an integer division
+__device__ __forceinline__ uint32_t div_g(const Params& p, uint32_t r) {
+  return p.G == 1 ? r : __umulhi(r, p.g_magic);
+}
 
 __device__ __forceinline__ int32_t list_len(const Params& p, int g) {
   return p.sel ? p.sel_count[g] : (int32_t)p.n;

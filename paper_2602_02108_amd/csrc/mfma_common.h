@@ -47,6 +47,33 @@ __device__ __forceinline__ uint4 lds_read16(const unsigned char* tile, int r, in
   return *reinterpret_cast<const uint4*>(tile + tile_off(r, c));
 }
 
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* glb_void_ptr;
+
+// s_waitcnt vmcnt(0): every outstanding vector-memory operation of this wave,
+// the direct global -> LDS loads included, has completed.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// One wave moves 16 rows (four 1 KiB chunks) of a natural tile straight from
+// global memory into LDS (global_load_lds_dwordx4: lane l writes 16 bytes at
+// LDS base + 16 l).  Lane l of a chunk lands at granule position l % 16 of row
+// l / 16, so it fetches the source granule that the swizzle maps there.
+// row0 must be a multiple of 16.  Completion: wait_vmem() + barrier.
+__device__ __forceinline__ void natural_rows_to_lds(const bf16_t* base, int64_t tok_stride, unsigned char* tile,
+                                                    int row0, int lane) {
+  // address = wave-uniform 64-bit base + 32-bit per-lane offset, so that nothing
+  // 64-bit and lane-dependent has to be kept in registers across the main loop
+  const uint32_t ts_bytes = (uint32_t)tok_stride * 2u;
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const uint32_t lrow = 4 * x + (lane >> 4);
+    const uint32_t c = (lane & 15) ^ (lrow & 15);
+    const char* sbase = reinterpret_cast<const char*>(base + (int64_t)row0 * tok_stride);
+    const char* src = sbase + (lrow * ts_bytes + c * 16u);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile + (row0 + 4 * x) * 256), 16, 0, 0);
+  }
+}
+
 // ---- natural tile: 128 tokens x 128 dims from a (page, head) slab ------------
 // NT threads cooperate; each holds 2048 / NT granules in registers between the
 // global load and the LDS store.
@@ -104,6 +131,66 @@ template <int NW> struct TransposedStage {
     }
   }
 };
+
+// Page list entries held in registers, 64 per window, two windows deep: lane j of a
+// window holds the logical page id of list entry base + j and its physical page.
+// The main loops read them with v_readlane, so no iteration waits for a chain of
+// dependent memory loads (selection list -> page table); the next window is
+// fetched while the current one is consumed.
+struct PageWindow {
+  int32_t l_cur, p_cur, l_nxt, p_nxt;
+  int32_t base;
+  static __device__ __forceinline__ void fetch(const Params& p, int g, int32_t len, int32_t b, int lane,
+                                               int32_t& l, int32_t& ph) {
+    const int32_t j = b + lane;
+    l = 0;
+    ph = 0;
+    if (j < len) {
+      l = list_at(p, g, j);
+      ph = p.page_table[l];
+    }
+  }
+  __device__ __forceinline__ void init(const Params& p, int g, int32_t len, int lane) {
+    base = 0;
+    fetch(p, g, len, 0, lane, l_cur, p_cur);
+    fetch(p, g, len, 64, lane, l_nxt, p_nxt);
+  }
+  // j (wave-uniform, non-decreasing across calls) must satisfy base <= j; entries up to
+  // j + 63 stay readable afterwards
+  __device__ __forceinline__ void advance(const Params& p, int g, int32_t len, int32_t j, int lane) {
+    if (j >= base + 64) {
+      l_cur = l_nxt;
+      p_cur = p_nxt;
+      base += 64;
+      fetch(p, g, len, base + 64, lane, l_nxt, p_nxt);
+    }
+  }
+  __device__ __forceinline__ int32_t page(int32_t j) const {
+    const int32_t k = j - base;
+    const int32_t a = __builtin_amdgcn_readlane(l_cur, k & 63), b = __builtin_amdgcn_readlane(l_nxt, k & 63);
+    return k < 64 ? a : b;
+  }
+  __device__ __forceinline__ int32_t phys(int32_t j) const {
+    const int32_t k = j - base;
+    const int32_t a = __builtin_amdgcn_readlane(p_cur, k & 63), b = __builtin_amdgcn_readlane(p_nxt, k & 63);
+    return k < 64 ? a : b;
+  }
+};
+
+// Number of leading list entries of KV head g whose logical page is <= l_max (the
+// list is ascending, so the invisible entries form a suffix).  64 entries per step,
+// one memory latency each.
+__device__ __forceinline__ int32_t visible_len(const Params& p, int g, int64_t l_max, int lane) {
+  int32_t len = list_len(p, g);
+  while (len > 0) {
+    const int32_t j = len - 1 - lane;
+    const bool over = j >= 0 && (int64_t)list_at(p, g, j) > l_max;
+    const int n_over = __builtin_popcountll(__ballot(over));
+    len -= n_over;
+    if (n_over < 64) break;
+  }
+  return len;
+}
 
 // max / sum across the two 32-lane halves of a wave (lanes l and l ^ 32).
 // permlane32_swap(v, v) returns {own, partner} in lanes < 32 and {partner, own}

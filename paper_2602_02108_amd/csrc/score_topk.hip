@@ -224,13 +224,13 @@ template <typename T, int D>
 static void launch_scoring(const Params& p, float* A, float* qbar, float* scores, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PER_BLOCK = 256 / LPR;
   const int units = p.Hq * p.m;
-  qpool_partial_kernel<T, D><<<dim3((units + PER_BLOCK - 1) / PER_BLOCK), dim3(256), 0, st>>>(p, A);
+  { ProfScope prof_("qpool_partial", st); qpool_partial_kernel<T, D><<<dim3((units + PER_BLOCK - 1) / PER_BLOCK), dim3(256), 0, st>>>(p, A); }
   const float r = 1.0f / (float)((int64_t)p.C * p.G);
-  qpool_final_kernel<<<dim3(p.Hkv), dim3(D), 0, st>>>(p, A, qbar, r);
+  { ProfScope prof_("qpool_final", st); qpool_final_kernel<<<dim3(p.Hkv), dim3(D), 0, st>>>(p, A, qbar, r); }
   if (p.n_past > 0) {
     const float inv_p = 1.0f / (float)p.P;
     dim3 grid((unsigned)((p.n_past + PER_BLOCK - 1) / PER_BLOCK), p.Hkv);
-    page_score_kernel<T, D><<<grid, dim3(256), 0, st>>>(p, qbar, scores, inv_p);
+    { ProfScope prof_("page_score", st); page_score_kernel<T, D><<<grid, dim3(256), 0, st>>>(p, qbar, scores, inv_p); }
   }
 }
 
@@ -270,8 +270,11 @@ hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32
   }
   const int64_t cap = lds_cap_bytes / 4;
   const int64_t cached = p.n_past < cap ? p.n_past : cap;
-  topk_select_kernel<<<dim3(p.Hkv), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
-      scores, p.n_past, p.m, top_k, sel, sel_count, (int32_t)cap);
+  {
+    ProfScope prof_("topk_select", st);
+    topk_select_kernel<<<dim3(p.Hkv), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
+        scores, p.n_past, p.m, top_k, sel, sel_count, (int32_t)cap);
+  }
   return hipGetLastError();
 }
 
