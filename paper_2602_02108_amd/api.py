@@ -114,6 +114,8 @@ def workspace_bytes(desc: AttnDesc, top_k: int, op: int) -> int:
 
 def _workspace(desc, top_k, op, device, workspace):
     need = workspace_bytes(desc, top_k, op)
+    if need == 0 and op != OP_SCORE_TOPK and top_k < 0:
+        need = workspace_bytes(desc, -1, op)
     if need == 0:
         raise OombError(ERR_INVALID_ARG, "oomb_workspace_bytes")
     if workspace is None:
@@ -160,8 +162,9 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
     """oomb_paged_attn_bwd.  Returns dQ; dk_pool / dv_pool are accumulated in place."""
     if d_q is None:
         d_q = torch.empty_like(q)
-    workspace, nbytes = _workspace(desc, 0, OP_ATTN_BWD, q.device, workspace)
     stride = 0 if sel_pages is None else int(sel_pages.stride(0))
+    list_k = -1 if sel_pages is None else stride - desc.chunk_len // desc.page_size
+    workspace, nbytes = _workspace(desc, list_k, OP_ATTN_BWD, q.device, workspace)
     st = lib().oomb_paged_attn_bwd(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
                                    _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(d_o), _p(d_q),
                                    _p(dk_pool), _p(dv_pool), _p(workspace), nbytes, _stream(q))

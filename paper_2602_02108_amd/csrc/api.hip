@@ -96,8 +96,11 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
     case OOMB_OP_ATTN_FWD:
       return 256;
     case OOMB_OP_ATTN_BWD: {
+      // longest selection list the call may be given: top_k retrieved pages + the m local pages
+      int64_t max_len = p.n;
+      if (top_k >= 0 && (int64_t)top_k + p.m < max_len) max_len = (int64_t)top_k + p.m;
       const size_t generic = up256((size_t)p.Hq * p.C * sizeof(float));
-      const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? bwd_mfma_workspace_bytes(p, (int32_t)p.n) : 0;
+      const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? bwd_mfma_workspace_bytes(p, (int32_t)max_len) : 0;
       return generic > mfma ? generic : mfma;
     }
     default:

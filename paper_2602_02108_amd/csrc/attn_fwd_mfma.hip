@@ -1,10 +1,11 @@
 // Paged attention forward with bf16 MFMA (paper Sec. 4.1 operator over the
 // selected pages of Sec. 4.2), page size 128, head dim 128.
 //
-// A workgroup of 8 waves owns 256 consecutive rows of one KV head's "row space":
-// row r = i * G + (h - g * G), i.e. the G query heads of the group interleaved
-// token by token, so the K/V tiles staged in LDS are shared by all query heads
-// of the group and a workgroup's rows span only 256 / G tokens (short causal
+// A workgroup of 8 waves owns 8 consecutive blocks of one KV head's "row space":
+// block b = tb * G + hd is the 32 consecutive chunk tokens 32 tb .. 32 tb + 31 of
+// query head g G + hd, i.e. the G query heads of the group interleaved block by
+// block, so the K/V tiles staged in LDS are shared by all query heads of the
+// group and a workgroup's rows span at most three token blocks (short causal
 // diagonal).  Each wave keeps its 32 query rows (as the B operand of
 // S^T = K Q^T) and its 32 x 128 output block in registers.  Pages are processed
 // as two half tiles of 64 keys: K as a natural half tile (direct global -> LDS
@@ -49,24 +50,20 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   if (tile >= tiles_per_head) return;
   tile = tiles_per_head - 1 - tile;  // rows late in the chunk see more local pages: start them first
 
-  const uint32_t rows_total = (uint32_t)p.C * p.G;
-  const uint32_t row0 = (uint32_t)tile * FW_ROWS;
+  // row space: block b = tb * G + hd holds tokens 32 tb .. 32 tb + 31 of head g G + hd;
+  // wave w of tile t owns block 8 t + w (one head, 32 consecutive tokens)
+  const int32_t nblk = (p.C / 32) * p.G;
   const int64_t first_q = p.N - p.C;
-
-  // this lane's query row
-  const uint32_t r_raw = row0 + wave * 32 + lq;
-  const bool r_valid = r_raw < rows_total;
-  const uint32_t r = r_valid ? r_raw : rows_total - 1;
-  const uint32_t i = div_g(p, r);
-  const int h = g * p.G + (int)(r - i * p.G);
+  const int32_t b_raw = tile * (FW_ROWS / 32) + wave;
+  const bool r_valid = b_raw < nblk;                       // wave-uniform
+  const uint32_t bw = (uint32_t)(r_valid ? b_raw : nblk - 1);
+  const uint32_t tbw = div_g(p, bw);
+  const uint32_t i = 32 * tbw + lq;
+  const int h = g * p.G + (int)(bw - tbw * p.G);
   const int64_t a_i = first_q + i;
-  // wave-uniform bounds of the wave's rows (for skipping / masking decisions)
-  const uint32_t rw_lo = row0 + wave * 32;
-  const uint32_t rw_hi = (rw_lo + 31 < rows_total) ? rw_lo + 31 : rows_total - 1;
-  const int64_t a_wave_min = first_q + div_g(p, rw_lo < rows_total ? rw_lo : rows_total - 1);
-  const int64_t a_wave_max = first_q + div_g(p, rw_hi);
-  const uint32_t rb_hi = (row0 + FW_ROWS - 1 < rows_total) ? row0 + FW_ROWS - 1 : rows_total - 1;
-  const int64_t a_blk_max = first_q + div_g(p, rb_hi);
+  const int64_t a_wave_min = first_q + 32 * tbw, a_wave_max = a_wave_min + 31;
+  const int32_t b_last = (tile * (FW_ROWS / 32) + 7 < nblk) ? tile * (FW_ROWS / 32) + 7 : nblk - 1;
+  const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)b_last) + 31;
 
   // number of half tiles visible to this workgroup (lists are ascending)
   const int32_t T = visible_len(p, g, a_blk_max / TP, lane);
