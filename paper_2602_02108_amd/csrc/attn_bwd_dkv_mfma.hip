@@ -154,17 +154,24 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
     const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
     nat_off[x] = (srow & 31) * ts_bytes + (((lane & 15) ^ (srow & 15)) << 4);
   }
-  auto load_natural = [&](int32_t s, unsigned char* sb) {
+  // (register staged: a direct global -> LDS load would make the compiler wait for it before
+  // the next LDS read, exposing the whole memory latency)
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 qn0, qn1, don0, don1;
+  auto load_natural = [&](int32_t s) {
     const int64_t bb = block_base(2 * s + (wave >> 2));
     const char* qb = reinterpret_cast<const char*>(p.q) + bb;
     const char* ob = reinterpret_cast<const char*>(p.d_o) + bb;
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)(qb + nat_off[x]), (lds_void_ptr)(sb + (8 * wave + 4 * x) * 256), 16,
-                                       0, 0);
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)(ob + nat_off[x]),
-                                       (lds_void_ptr)(sb + 16384 + (8 * wave + 4 * x) * 256), 16, 0, 0);
-    }
+    qn0 = *reinterpret_cast<const u32x4*>(qb + nat_off[0]);
+    don0 = *reinterpret_cast<const u32x4*>(ob + nat_off[0]);
+    qn1 = *reinterpret_cast<const u32x4*>(qb + nat_off[1]);
+    don1 = *reinterpret_cast<const u32x4*>(ob + nat_off[1]);
+  };
+  auto store_natural = [&](unsigned char* sb) {
+    *reinterpret_cast<u32x4*>(sb + (8 * wave) * 256 + lane * 16) = qn0;
+    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave) * 256 + lane * 16) = don0;
+    *reinterpret_cast<u32x4*>(sb + (8 * wave + 4) * 256 + lane * 16) = qn1;
+    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave + 4) * 256 + lane * 16) = don1;
   };
   // transposed tiles: this wave owns octet `wave` = rows 16 u + 4 h2 + {0..3, 8..11} of the stage
   // (block 2 s + (u >> 1), tokens 16 (u & 1) + ...), lane l the dims 2 l, 2 l + 1
@@ -206,140 +213,147 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
     for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(xch + k * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
   }
   if (nb > 0) {
-    load_natural(s0, smem + (s0 & 1) * KV_STAGE);
+    load_natural(s0);
     load_transposed(s0);
+    store_natural(smem + (s0 & 1) * KV_STAGE);
     store_transposed(smem + (s0 & 1) * KV_STAGE);
   }
-  wait_vmem();
   __syncthreads();
 
-  // Both roles run nb + 1 steps with one barrier each (role 1 works one block behind).
-  // Step `step` covers block blk = 2 s0 + step; the first step of a stage starts the
-  // fetch of the next stage, the second one finishes it (transposed tiles -> LDS).
+  // One loop iteration = one stage = two blocks, two barriers.  The next stage is fetched
+  // into registers at the top and written to the other LDS buffer at the bottom (the last
+  // iteration re-fetches its own stage; nobody reads that copy).  Role 1 works one block
+  // behind role 0 and finishes with one extra half step.  All code between barriers is
+  // straight-line so that no register array needs copies at control-flow joins.
+  const int32_t tok_first = (int32_t)(first - first_q);
   if (nb > 0) {
     if (role == 0) {
-      float stat_next = stat_rs[(int64_t)64 * s0] * stat_scale;
-      for (int32_t step = 0; step <= nb; ++step) {
-        const int32_t blk = 2 * s0 + step, s = blk >> 1, half = blk & 1;
+      // S = Q K^T - LSE / c, P = exp2(c S) (masked), P -> partner, dV^T += dO^T P
+      auto block0 = [&](const int32_t blk, const unsigned char* sb, const int half, const float stat_raw) {
+        f32x16 sc;
+        uint4 fa[4], fb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[k] + half * 8192);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + na[4 + k] + half * 8192);
+        const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int x = 0; x < 16; ++x) sc[x] = 0.f;
+        sc = mfma32(bias, ones, sc);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fa[k]), kvf[k], sc);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char* dt = sb + 49152;  // dO^T fragments for the dV product of this block
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 0] + k * 4096);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fb[k]), kvf[4 + k], sc);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 1] + k * 4096);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
+        const int32_t tok0 = 32 * (int32_t)div_g(p, (uint32_t)blk);  // first chunk token of the block
+        if (tok0 < tok_first + TP - 1) {                              // diagonal block: rows before the key see nothing
+          const int32_t rel = key_rel - tok0 - 4 * hh;
+#pragma unroll
+          for (int x = 0; x < 16; ++x)
+            if (8 * (x >> 2) + (x & 3) < rel) sc[x] = 0.f;
+        }
+        const uint4 p0 = kv_pack8(sc, 0), p1 = kv_pack8(sc, 8);
+        unsigned char* xb = xch + (blk & 1) * 2048;
+        *reinterpret_cast<uint4*>(xb + lane * 16) = p0;
+        *reinterpret_cast<uint4*>(xb + 1024 + lane * 16) = p1;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fa[db]), as_bf16x8(p0), acc[db]);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fb[db]), as_bf16x8(p1), acc[db]);
+      };
+      float st_a = stat_rs[(int64_t)64 * s0], st_b;
+      for (int32_t s = s0; s < s1; ++s) {
         const unsigned char* sb = smem + (s & 1) * KV_STAGE;
-        const bool have = step < nb;
-        if (have && half == 0 && s + 1 < s1) {
-          load_natural(s + 1, smem + ((s + 1) & 1) * KV_STAGE);
-          load_transposed(s + 1);
-        }
-        if (have) {
-          const float stat = stat_next;
-          if (step + 1 < nb) stat_next = stat_rs[(int64_t)32 * (blk + 1)] * stat_scale;
-          // S = Q K^T - LSE / c
-          f32x16 sc;
-          uint4 fa[4], fb[4];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[k] + half * 8192);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + na[4 + k] + half * 8192);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int x = 0; x < 16; ++x) sc[x] = 0.f;
-          sc = mfma32(bias_frag(stat, hh), ones, sc);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fa[k]), kvf[k], sc);
-          __builtin_amdgcn_sched_barrier(0);
-          const unsigned char* dt = sb + 49152;  // dO^T fragments for the dV product of this block
-#pragma unroll
-          for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 0] + k * 4096);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fb[k]), kvf[4 + k], sc);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 1] + k * 4096);
-          __builtin_amdgcn_sched_barrier(0);
-          // P = exp2(c S); rows that do not see this lane's key get 0
-#pragma unroll
-          for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
-          const int32_t tok0 = 32 * (int32_t)div_g(p, (uint32_t)blk);  // first chunk token of the block
-          if (tok0 < (int32_t)(first - first_q) + TP - 1) {            // diagonal block
-            const int32_t rel = key_rel - tok0 - 4 * hh;
-#pragma unroll
-            for (int x = 0; x < 16; ++x)
-              if (8 * (x >> 2) + (x & 3) < rel) sc[x] = 0.f;
-          }
-          const uint4 p0 = kv_pack8(sc, 0), p1 = kv_pack8(sc, 8);
-          unsigned char* xb = xch + (blk & 1) * 2048;
-          *reinterpret_cast<uint4*>(xb + lane * 16) = p0;
-          *reinterpret_cast<uint4*>(xb + 1024 + lane * 16) = p1;
-          // dV^T += dO^T P
-#pragma unroll
-          for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fa[db]), as_bf16x8(p0), acc[db]);
-#pragma unroll
-          for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fb[db]), as_bf16x8(p1), acc[db]);
-        }
-        if (have && half == 1 && s + 1 < s1) store_transposed(smem + ((s + 1) & 1) * KV_STAGE);
-        wait_vmem();
+        unsigned char* nsb = smem + ((s + 1) & 1) * KV_STAGE;
+        const int32_t sn = s + 1 < s1 ? s + 1 : s;
+        load_natural(sn);
+        load_transposed(sn);
+        st_b = stat_rs[(int64_t)64 * s + 32];
+        block0(2 * s, sb, 0, st_a);
+        __syncthreads();
+        st_a = stat_rs[(int64_t)64 * sn];
+        block0(2 * s + 1, sb, 1, st_b);
+        store_natural(nsb);
+        store_transposed(nsb);
         __syncthreads();
       }
     } else {
-      // dP = dO V^T - Delta of this block; dS = P o dP and dK^T += Q^T dS of the previous block.
-      // Straight-line body: in the first step the "previous block" multiplies zeros (the P
-      // exchange was cleared, dp_prev = 0) with a valid Q tile; in the last step the dP product
-      // of a non-existent block is computed from stale LDS and never used.
-      f32x16 dp_prev;
-#pragma unroll
-      for (int x = 0; x < 16; ++x) dp_prev[x] = 0.f;
-      float stat_next = stat_rs[(int64_t)64 * s0] * stat_scale;
-      for (int32_t step = 0; step <= nb; ++step) {
-        const int32_t blk = 2 * s0 + step, s = blk >> 1, half = blk & 1;
-        const unsigned char* sb = smem + (s & 1) * KV_STAGE;
-        const bool have = step < nb;
-        if (have && half == 0 && s + 1 < s1) {
-          load_natural(s + 1, smem + ((s + 1) & 1) * KV_STAGE);
-          load_transposed(s + 1);
-        }
-        const float stat = stat_next;
-        if (step + 1 < nb) stat_next = stat_rs[(int64_t)32 * (blk + 1)] * stat_scale;
-        const int32_t pb = step >= 1 ? blk - 1 : blk, ps = pb >> 1, ph = pb & 1;
-        const unsigned char* qtile = smem + (ps & 1) * KV_STAGE + 32768;
-        const unsigned char* xb = xch + ((blk - 1) & 1) * 2048;
-        f32x16 dp;
+      // dS = P o dP of the previous block (vector work first), dK^T += Q^T dS, then
+      // dP = dO V^T - Delta of the current block.  The partner wave on this SIMD starts its
+      // step with matrix work and does its vector work in the middle, so the two waves keep
+      // both pipes busy.  dprev is consumed, dcur produced.
+      auto prev_part = [&](f32x16& dprev, const unsigned char* qtile, const int ph, const unsigned char* xb) {
         uint4 fa[4], fb[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[k] + half * 8192);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[4 + k] + half * 8192);
         const uint4 p0 = *reinterpret_cast<const uint4*>(xb + lane * 16);
         const uint4 p1 = *reinterpret_cast<const uint4*>(xb + 1024 + lane * 16);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int x = 0; x < 16; ++x) dp[x] = 0.f;
-        dp = mfma32(bias_frag(stat, hh), ones, dp);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) dp = mfma32(as_bf16x8(fa[k]), kvf[k], dp);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(qtile + ta[2 * ph + 0] + k * 4096);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) dp = mfma32(as_bf16x8(fb[k]), kvf[4 + k], dp);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(qtile + ta[2 * ph + 1] + k * 4096);
         __builtin_amdgcn_sched_barrier(0);
         const uint32_t pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          dp_prev[2 * k] *= __uint_as_float(pw[k] << 16);
-          dp_prev[2 * k + 1] *= __uint_as_float(pw[k] & 0xffff0000u);
+          dprev[2 * k] *= __uint_as_float(pw[k] << 16);
+          dprev[2 * k + 1] *= __uint_as_float(pw[k] & 0xffff0000u);
         }
-        const uint4 s0v = kv_pack8(dp_prev, 0), s1v = kv_pack8(dp_prev, 8);
+        const uint4 s0v = kv_pack8(dprev, 0), s1v = kv_pack8(dprev, 8);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fa[db]), as_bf16x8(s0v), acc[db]);
 #pragma unroll
         for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fb[db]), as_bf16x8(s1v), acc[db]);
-        dp_prev = dp;
-        if (have && half == 1 && s + 1 < s1) store_transposed(smem + ((s + 1) & 1) * KV_STAGE);
-        wait_vmem();
+      };
+      auto cur_part = [&](f32x16& dcur, const unsigned char* sb, const int half, const float stat_raw) {
+        uint4 fa[4], fb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[k] + half * 8192);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[4 + k] + half * 8192);
+        const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
+#pragma unroll
+        for (int x = 0; x < 16; ++x) dcur[x] = 0.f;
+        __builtin_amdgcn_sched_barrier(0);
+        dcur = mfma32(bias, ones, dcur);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dcur = mfma32(as_bf16x8(fa[k]), kvf[k], dcur);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dcur = mfma32(as_bf16x8(fb[k]), kvf[4 + k], dcur);
+      };
+      f32x16 dpa, dpb;  // dP of even / odd blocks
+#pragma unroll
+      for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
+      float st_a = stat_rs[(int64_t)64 * s0], st_b;
+      for (int32_t s = s0; s < s1; ++s) {
+        const unsigned char* sb = smem + (s & 1) * KV_STAGE;
+        unsigned char* nsb = smem + ((s + 1) & 1) * KV_STAGE;
+        const int32_t sn = s + 1 < s1 ? s + 1 : s;
+        load_natural(sn);
+        load_transposed(sn);
+        st_b = stat_rs[(int64_t)64 * s + 32];
+        // previous block 2 s - 1 lives in the other stage buffer (for s == s0: zeros times this stage's tile)
+        prev_part(dpb, (s > s0 ? nsb : sb) + 32768, 1, xch + 2048);
+        cur_part(dpa, sb, 0, st_a);
+        __syncthreads();
+        st_a = stat_rs[(int64_t)64 * sn];
+        prev_part(dpa, sb + 32768, 0, xch);
+        cur_part(dpb, sb, 1, st_b);
+        store_natural(nsb);
+        store_transposed(nsb);
         __syncthreads();
       }
+      prev_part(dpb, smem + ((s1 - 1) & 1) * KV_STAGE + 32768, 1, xch + 2048);
     }
   }
 
