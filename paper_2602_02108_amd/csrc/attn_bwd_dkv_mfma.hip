@@ -409,12 +409,13 @@ size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split) {
   return (size_t)p.Hkv * (size_t)max_len * (size_t)n_split * 2 * TP * HD * sizeof(float);
 }
 
-// Slices per page: enough units to keep 256 CUs busy in whole rounds without making the
-// second-stage reduction large.
+// Slices per page: enough units (about 8 rounds of 256 workgroups) for the tail of the last
+// round to be short, without making the second-stage reduction large.
 int32_t dkv_splits(const Params& p, int32_t max_len) {
   const int64_t units = (int64_t)p.Hkv * max_len;
-  if (units >= 1536) return 1;
-  return 2;
+  if (units <= 0) return 1;
+  const int64_t want = (2048 + units - 1) / units;
+  return (int32_t)(want < 1 ? 1 : (want > 4 ? 4 : want));
 }
 
 hipError_t launch_bwd_dkv_mfma(const Params& p, const float* delta_rs, const float* lse2_rs, int64_t rows_pad,

@@ -88,47 +88,19 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restri
 
 // ---------------------------------------------------------------------------------
 // dQ.  LDS: two stages of {K natural half tile, V natural half tile, K transposed
-// half tile}, 16 KiB each.
+// half tile}, 16 KiB each.  One barrier per half tile of 64 keys; the next half tile
+// is fetched into registers at the top of an iteration and written to the other
+// stage at its bottom.
 constexpr int DQ_STAGE = 3 * 16384;
 constexpr int DQ_LDS = 2 * DQ_STAGE;
-
-struct DqStage {
-  uint4 kn[2], vn[2];
-  uint32_t kt[8];
-  // half tile hf of the page at kb / vb
-  __device__ __forceinline__ void load(const bf16_t* kb, const bf16_t* vb, int64_t ts, int hf, int tid, int wave,
-                                       int lane) {
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int gi = tid + BW_THREADS * x;
-      const int64_t o = (int64_t)(64 * hf + (gi >> 4)) * ts + (gi & 15) * 8;
-      kn[x] = *reinterpret_cast<const uint4*>(kb + o);
-      vn[x] = *reinterpret_cast<const uint4*>(vb + o);
-    }
-    const int u = wave >> 1, h2 = wave & 1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = 64 * hf + 16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2);
-      kt[e] = *reinterpret_cast<const uint32_t*>(kb + (int64_t)tok * ts + 2 * lane);
-    }
-  }
-  __device__ __forceinline__ void store(unsigned char* st, int tid, int wave, int lane) const {
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int gi = tid + BW_THREADS * x;
-      *reinterpret_cast<uint4*>(st + toff<16>(gi >> 4, gi & 15)) = kn[x];
-      *reinterpret_cast<uint4*>(st + 16384 + toff<16>(gi >> 4, gi & 15)) = vn[x];
-    }
-    *reinterpret_cast<uint4*>(st + 32768 + toff<8>(2 * lane, wave)) = pack_hi_lo(kt, 0x05040100u);
-    *reinterpret_cast<uint4*>(st + 32768 + toff<8>(2 * lane + 1, wave)) = pack_hi_lo(kt, 0x07060302u);
-  }
-};
 
 __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const float* __restrict__ delta_rs,
                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
                                                             int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hh = lane >> 5, lq = lane & 31;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int g, tile;
   if (xcd_map) {
     const int xcd = blockIdx.x & 7, per = 8 / p.Hkv;
@@ -156,11 +128,11 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   const int32_t b_last = (tile * (DQ_ROWS / 32) + 7 < nblk) ? tile * (DQ_ROWS / 32) + 7 : nblk - 1;
   const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)b_last) + 31;
 
-  int32_t T = list_len(p, g);
-  {
-    const int64_t l_max = a_blk_max / TP;
-    while (T > 0 && list_at(p, g, T - 1) > l_max) --T;
-  }
+  const int32_t T = visible_len(p, g, a_blk_max / TP, lane);
+  PageWindow pw;
+  pw.init(p, g, T, lane);
+  int32_t T2 = 2 * T;
+  if (T > 0 && (int64_t)list_at(p, g, T - 1) * TP + 64 > a_blk_max) T2 -= 1;  // second half of the last page unseen
 
   const int64_t roff = (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
   bf16x8 qf[8], dof[8];
@@ -179,65 +151,140 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
 #pragma unroll
     for (int x = 0; x < 16; ++x) dq[db][x] = 0.f;
 
-  DqStage stg;
-  auto tile_ptrs = [&](int32_t j, const bf16_t*& kb, const bf16_t*& vb, int64_t& first) {
-    const int64_t l = list_at(p, g, j);
-    const int64_t off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
-    kb = (const bf16_t*)p.k_pool + off;
-    vb = (const bf16_t*)p.v_pool + off;
-    first = l * TP;
+  // LDS operand addresses: (lane base ^ constant) + immediate
+  uint32_t na[8], ta[4];
+  {
+    const uint32_t nbase = lq * 256 + (((lq & 15) ^ hh) << 4);          // natural tiles, 16 granules per row
+    const uint32_t tbase = lq * 128 + ((((lq >> 1) & 7) ^ hh) << 4);    // transposed tile, 8 granules per row
+#pragma unroll
+    for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) ta[k] = tbase ^ (k << 5);
+  }
+
+  // half tile ht: page ht / 2, keys 64 (ht % 2) .. + 63
+  auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
+  auto ht_off = [&](int32_t ht) -> int64_t {
+    return (int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
+           (int64_t)(ht & 1) * 64 * p.pool_tok_stride;
   };
-  const bf16_t *kb = nullptr, *vb = nullptr;
-  int64_t first = 0, first_cur = 0;
-  const int32_t n_st = 2 * T;
-  if (n_st > 0) {
-    tile_ptrs(0, kb, vb, first);
-    stg.load(kb, vb, p.pool_tok_stride, 0, tid, wave, lane);
-    stg.store(smem, tid, wave, lane);
+  // staging registers: this wave's 8 rows of the natural K and V half tiles (two 4-row
+  // chunks each, source granule pre-swizzled) and its octet of the transposed K half tile
+  const uint32_t ts_bytes = (uint32_t)p.pool_tok_stride * 2u;
+  uint32_t nat_off[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
+    nat_off[x] = srow * ts_bytes + (((lane & 15) ^ (srow & 15)) << 4);
+  }
+  u32x4 kn0, kn1, vn0, vn1;
+  uint32_t kt[8];
+  auto load_stage = [&](int32_t ht) {
+    const int64_t off = ht_off(ht) * 2;
+    const char* kb = reinterpret_cast<const char*>(p.k_pool) + off;
+    const char* vb = reinterpret_cast<const char*>(p.v_pool) + off;
+    kn0 = *reinterpret_cast<const u32x4*>(kb + nat_off[0]);
+    vn0 = *reinterpret_cast<const u32x4*>(vb + nat_off[0]);
+    kn1 = *reinterpret_cast<const u32x4*>(kb + nat_off[1]);
+    vn1 = *reinterpret_cast<const u32x4*>(vb + nat_off[1]);
+    const int u = wave >> 1, h2 = wave & 1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t ro = (uint32_t)(16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2)) * ts_bytes;  // wave-uniform
+      kt[e] = *reinterpret_cast<const uint32_t*>(kb + ro + (uint32_t)lane * 4u);
+    }
+  };
+  const int tr_o0 = ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = ((2 * lane + 1) * 8 + (wave ^ (lane & 7))) * 16;
+  auto store_stage = [&](unsigned char* sb) {
+    *reinterpret_cast<u32x4*>(sb + (8 * wave) * 256 + lane * 16) = kn0;
+    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave) * 256 + lane * 16) = vn0;
+    *reinterpret_cast<u32x4*>(sb + (8 * wave + 4) * 256 + lane * 16) = kn1;
+    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave + 4) * 256 + lane * 16) = vn1;
+    *reinterpret_cast<uint4*>(sb + 32768 + tr_o0) = pack_hi_lo(kt, 0x05040100u);
+    *reinterpret_cast<uint4*>(sb + 32768 + tr_o1) = pack_hi_lo(kt, 0x07060302u);
+  };
+
+  // S^T, dP^T of one 32-key block kb2 of the half tile in sb; dS^T (bf16) into dsf[2 kb2 ..]
+  bf16x8 dsf[4];
+  auto block = [&](const unsigned char* sb, const int kb2, const bool diag, const int rel) {
+    f32x16 sv, dp;
+    uint4 fa[4], fb[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[k] + kb2 * 8192);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[k] + kb2 * 8192);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int x = 0; x < 16; ++x) { sv[x] = 0.f; dp[x] = 0.f; }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      sv = mfma32(as_bf16x8(fa[k]), qf[k], sv);
+      dp = mfma32(as_bf16x8(fb[k]), dof[k], dp);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[4 + k] + kb2 * 8192);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[4 + k] + kb2 * 8192);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      sv = mfma32(as_bf16x8(fa[k]), qf[4 + k], sv);
+      dp = mfma32(as_bf16x8(fb[k]), dof[4 + k], dp);
+    }
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], c, -lse2));
+      if (diag && 32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) pr = 0.f;
+      sv[x] = pr * (dp[x] - dlt);
+    }
+    dsf[2 * kb2 + 0] = as_bf16x8(pack8(sv, 0));
+    dsf[2 * kb2 + 1] = as_bf16x8(pack8(sv, 8));
+  };
+
+  if (T2 > 0) {
+    load_stage(0);
+    store_stage(smem);
   }
   __syncthreads();
 
-  for (int32_t st = 0; st < n_st; ++st) {
-    const int b = st & 1, hf = st & 1;  // stage parity doubles as the half index
-    const unsigned char* sb = smem + b * DQ_STAGE;
-    first_cur = first;
-    if (st + 1 < n_st) {
-      if (((st + 1) & 1) == 0) tile_ptrs((st + 1) >> 1, kb, vb, first);
-      stg.load(kb, vb, p.pool_tok_stride, (st + 1) & 1, tid, wave, lane);
-    }
-    const int64_t kfirst = first_cur + 64 * hf;
-    if (kfirst <= a_wave_max) {
+  for (int32_t t = 0; t < T2; ++t) {
+    pw.advance(p, g, T, t >> 1, lane);
+    const unsigned char* sb = smem + (t & 1) * DQ_STAGE;
+    const bool more = t + 1 < T2;
+    if (more) load_stage(t + 1);
+    const int64_t kfirst = ht_first(t);
+    if (kfirst <= a_wave_max) {  // wave-uniform: some row of this wave sees the half tile
       const bool diag = kfirst + 63 > a_wave_min;
-      bf16x8 dsf[4];
+      const int rel = (int)(a_i - kfirst) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
+      block(sb, 0, diag, rel);
+      block(sb, 1, diag, rel);
+      // dQ^T += K^T dS^T
+      uint4 fa[4], fb[4];
+      const unsigned char* kt_tile = sb + 32768;
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2) {
-        f32x16 s, dp;
+      for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u]);
 #pragma unroll
-        for (int x = 0; x < 16; ++x) { s[x] = 0.f; dp[x] = 0.f; }
+      for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 4096);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          s = mfma32(lds_frag<16>(sb, 32 * kb2 + lq, 2 * kk + hh), qf[kk], s);
-          dp = mfma32(lds_frag<16>(sb + 16384, 32 * kb2 + lq, 2 * kk + hh), dof[kk], dp);
-        }
+      for (int u = 0; u < 4; ++u) dq[0] = mfma32(as_bf16x8(fa[u]), dsf[u], dq[0]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -lse2));
-          if (diag) {
-            const int64_t key = kfirst + 32 * kb2 + 8 * (x >> 2) + 4 * hh + (x & 3);
-            if (key > a_i) pr = 0.f;
-          }
-          s[x] = pr * (dp[x] - dlt);
-        }
-        dsf[2 * kb2 + 0] = as_bf16x8(pack8(s, 0));
-        dsf[2 * kb2 + 1] = as_bf16x8(pack8(s, 8));
-      }
+      for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 2 * 4096);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+      for (int u = 0; u < 4; ++u) dq[1] = mfma32(as_bf16x8(fb[u]), dsf[u], dq[1]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          dq[db] = mfma32(lds_frag<8>(sb + 32768, 32 * db + lq, 2 * u + hh), dsf[u], dq[db]);
+      for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 3 * 4096);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) dq[2] = mfma32(as_bf16x8(fa[u]), dsf[u], dq[2]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) dq[3] = mfma32(as_bf16x8(fb[u]), dsf[u], dq[3]);
     }
-    if (st + 1 < n_st) stg.store(smem + (b ^ 1) * DQ_STAGE, tid, wave, lane);
+    if (more) store_stage(smem + ((t + 1) & 1) * DQ_STAGE);
     __syncthreads();
   }
 
