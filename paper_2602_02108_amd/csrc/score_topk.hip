@@ -79,10 +79,22 @@ __global__ __launch_bounds__(256) void qpool_partial_kernel(Params p, float* __r
 __global__ void qpool_final_kernel(Params p, const float* __restrict__ A, float* __restrict__ qbar, float r) {
   const int g = blockIdx.x, d = threadIdx.x;
   if (d >= p.D) return;
+  // flat index k = tau * G + (h - g G) walks the sum in its fixed order; loads are issued 32 at a
+  // time (they are independent), the additions stay sequential
+  const int n = p.m * p.G;
   float acc = 0.0f;
-  for (int tau = 0; tau < p.m; ++tau)
-    for (int h = g * p.G; h < g * p.G + p.G; ++h)
-      acc = __fadd_rn(acc, A[((int64_t)h * p.m + tau) * p.D + d]);
+  for (int k0 = 0; k0 < n; k0 += 32) {
+    float v[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const int k = k0 + u < n ? k0 + u : n - 1;
+      const int tau = k / p.G, h = g * p.G + (k - tau * p.G);
+      v[u] = A[((int64_t)h * p.m + tau) * p.D + d];
+    }
+#pragma unroll
+    for (int u = 0; u < 32; ++u)
+      if (k0 + u < n) acc = __fadd_rn(acc, v[u]);
+  }
   qbar[g * p.D + d] = __fmul_rn(acc, r);
 }
 
@@ -128,13 +140,14 @@ __device__ __forceinline__ uint32_t order_key(float s) {
 
 constexpr int SELECT_THREADS = 1024;
 
-__device__ __forceinline__ int block_sum(int v, int* smem /*[17]*/) {
+// block-wide sum of a 64-bit value (used for three 21-bit counters packed in one word)
+__device__ __forceinline__ unsigned long long block_sum64(unsigned long long v, unsigned long long* smem /*[16]*/) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
   __syncthreads();  // protects smem reuse across calls
   if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
   __syncthreads();
-  int tot = 0;
+  unsigned long long tot = 0;
 #pragma unroll
   for (int w = 0; w < SELECT_THREADS / 64; ++w) tot += smem[w];
   return tot;
@@ -148,8 +161,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
     const float* __restrict__ scores, int64_t n_past, int32_t m, int32_t top_k,
     int32_t* __restrict__ sel, int32_t* __restrict__ sel_count, int32_t lds_cap) {
   extern __shared__ uint32_t keys[];  // first min(n_past, lds_cap) keys cached
-  __shared__ int red[SELECT_THREADS / 64 + 1];
-  __shared__ int scan_w[SELECT_THREADS / 64];
+  __shared__ unsigned long long red[SELECT_THREADS / 64];
   const int g = blockIdx.x, tid = threadIdx.x;
   const float* sc = scores + (int64_t)g * n_past;
   const int32_t stride = top_k + m;
@@ -161,18 +173,28 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
   __syncthreads();
   auto key_at = [&](int64_t l) -> uint32_t { return l < cached ? keys[l] : order_key(sc[l]); };
 
+  // T = the k_eff-th largest key = the largest T with #(key >= T) >= k_eff, found two bits at
+  // a time: the counts for the three candidates T | (1..3 << b) travel in one 64-bit sum
+  // (21 bits each; n_past <= 2^20).
   uint32_t T = 0;
   int take_eq = 0;
   if (k_eff > 0) {
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
-      int c = 0;
-      for (int64_t l = tid; l < n_past; l += SELECT_THREADS) c += key_at(l) >= cand;
-      if (block_sum(c, red) >= k_eff) T = cand;
+    for (int b = 30; b >= 0; b -= 2) {
+      const uint32_t c1 = T | (1u << b), c2 = T | (2u << b), c3 = T | (3u << b);
+      unsigned long long c = 0;
+      for (int64_t l = tid; l < n_past; l += SELECT_THREADS) {
+        const uint32_t k = key_at(l);
+        c += (unsigned long long)(k >= c1) | ((unsigned long long)(k >= c2) << 21) | ((unsigned long long)(k >= c3) << 42);
+      }
+      const unsigned long long tot = block_sum64(c, red);
+      const int n1 = (int)(tot & 0x1fffff), n2 = (int)((tot >> 21) & 0x1fffff), n3 = (int)((tot >> 42) & 0x1fffff);
+      if (n3 >= k_eff) T = c3;
+      else if (n2 >= k_eff) T = c2;
+      else if (n1 >= k_eff) T = c1;
     }
-    int c = 0;
+    unsigned long long c = 0;
     for (int64_t l = tid; l < n_past; l += SELECT_THREADS) c += key_at(l) > T;
-    take_eq = k_eff - block_sum(c, red);  // how many keys equal to T are kept (lowest ids)
+    take_eq = k_eff - (int)block_sum64(c, red);  // how many keys equal to T are kept (lowest ids)
   }
 
   // ordered emission: thread t owns the contiguous id range [t*per, (t+1)*per)
@@ -217,7 +239,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
   for (int32_t j = tid; j < m; j += SELECT_THREADS) out[k_eff + j] = (int32_t)(n_past + j);
   for (int32_t j = k_eff + m + tid; j < stride; j += SELECT_THREADS) out[j] = -1;
   if (tid == 0) sel_count[g] = k_eff + m;
-  (void)scan_w;
 }
 
 template <typename T, int D>

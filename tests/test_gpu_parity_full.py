@@ -1,0 +1,151 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py
+times.  The oracle cannot run these whole, so: page selection is compared in full
+(bit-exact), O / LSE / dQ on sampled query rows, dK / dV on sampled (KV head, page)
+units where the oracle can afford the row statistics of a whole head group, and
+otherwise through identities that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2602_02108_amd import api
+from paper_2602_02108_amd.workloads import WORKLOADS, make_inputs, to_numpy, torch_dtype
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(w, n_rand, seed):
+    rng = np.random.default_rng(seed)
+    rows = {(0, 0), (w.Hq - 1, w.C - 1), (0, w.C - 1), (w.Hq - 1, 0)}
+    for i in (w.P - 1, w.P, w.C // 2 - 1, w.C // 2, w.C - w.P, 31, 32):   # page and block boundaries
+        for h in (0, w.G - 1, w.G, w.Hq - 1):
+            rows.add((h, i))
+    while len(rows) < n_rand:
+        rows.add((int(rng.integers(w.Hq)), int(rng.integers(w.C))))
+    return np.array(sorted(rows), dtype=np.int32)
+
+
+def _run_gpu(w, x):
+    sel = cnt = None
+    if w.top_k is not None:
+        sel, cnt, scores = pu.gpu_select(w, x)
+    else:
+        scores = None
+    res = pu.gpu_fwd_bwd(w, x, sel, cnt)
+    return sel, cnt, scores, res
+
+
+def _check_rows(w, hx, res, osel, ocnt, rows, lse_full=None, delta_full=None):
+    sh = pu.shape_of(w)
+    o_r, lse_r = orc.attn_fwd(sh, hx["q"], hx["k_pool"], hx["v_pool"], hx["page_table"], osel, ocnt, rows=rows)
+    o_gpu = pu.f32(res["o"])[rows[:, 1], rows[:, 0]]
+    lse_gpu = pu.f32(res["lse"])[rows[:, 0], rows[:, 1]]
+    pu.check("O (sampled rows)", o_gpu, o_r, w.dtype)
+    pu.check("LSE (sampled rows)", lse_gpu, lse_r, "bf16")
+    # Delta for the sampled rows from the oracle's own O
+    d_o = torch.from_numpy(hx["d_o"].view(np.int16)).view(torch.bfloat16).float().numpy()
+    lse = np.zeros((w.Hq, w.C), dtype=np.float32)
+    dl = np.zeros((w.Hq, w.C), dtype=np.float32)
+    lse[rows[:, 0], rows[:, 1]] = lse_r
+    dl[rows[:, 0], rows[:, 1]] = (d_o[rows[:, 1], rows[:, 0]] * o_r).sum(axis=1)
+    dq_r = orc.attn_bwd_dq(sh, hx["q"], hx["k_pool"], hx["v_pool"], hx["page_table"], lse, dl, hx["d_o"], osel, ocnt,
+                           rows=rows)
+    pu.check("dQ (sampled rows)", pu.f32(res["dq"])[rows[:, 1], rows[:, 0]], dq_r, w.dtype)
+
+
+def _check_units(w, hx, res, osel, ocnt, g, pages):
+    """dK / dV of a few pages of KV head g: the oracle needs LSE / Delta of every row of the group."""
+    sh = pu.shape_of(w)
+    heads = np.arange(g * w.G, (g + 1) * w.G)
+    rows = np.array([(h, i) for h in heads for i in range(w.C)], dtype=np.int32)
+    o_r, lse_r = orc.attn_fwd(sh, hx["q"], hx["k_pool"], hx["v_pool"], hx["page_table"], osel, ocnt, rows=rows)
+    d_o = torch.from_numpy(hx["d_o"].view(np.int16)).view(torch.bfloat16).float().numpy()
+    lse = np.zeros((w.Hq, w.C), dtype=np.float32)
+    dl = np.zeros((w.Hq, w.C), dtype=np.float32)
+    lse[rows[:, 0], rows[:, 1]] = lse_r
+    dl[rows[:, 0], rows[:, 1]] = (d_o[rows[:, 1], rows[:, 0]] * o_r).sum(axis=1)
+    units = np.array([(g, int(l)) for l in pages], dtype=np.int32)
+    # small pools holding only the sampled pages' slots would need remapping; use sparse dicts instead
+    dk = np.zeros(hx["k_pool"].shape, dtype=np.float32)
+    dv = np.zeros(hx["k_pool"].shape, dtype=np.float32)
+    orc.attn_bwd_dkv(sh, hx["q"], hx["k_pool"], hx["v_pool"], hx["page_table"], lse, dl, hx["d_o"], dk, dv, osel, ocnt,
+                     units=units)
+    phys = hx["page_table"][np.asarray(pages)]
+    idx = torch.as_tensor(phys, device=res["dk_pool"].device).long()
+    gd = "bf16"
+    pu.check("dK (sampled pages)", pu.f32(res["dk_pool"][idx, g]), dk[phys, g], gd)
+    pu.check("dV (sampled pages)", pu.f32(res["dv_pool"][idx, g]), dv[phys, g], gd)
+
+
+def _check_identities(w, x, res):
+    """<dV, V> = sum <dO, O> and <dK, K> = <dQ, Q> per KV head group (pools started at zero)."""
+    for g in range(w.Hkv):
+        hs = slice(g * w.G, (g + 1) * w.G)
+        lhs_v = (res["dv_pool"][:, g].double() * x["v_pool"][:, g].double()).sum().item()
+        rhs_v = (x["d_o"][:, hs].double() * res["o"][:, hs].double()).sum().item()
+        lhs_k = (res["dk_pool"][:, g].double() * x["k_pool"][:, g].double()).sum().item()
+        rhs_k = (res["dq"][:, hs].double() * x["q"][:, hs].double()).sum().item()
+        # both sides are sums of ~1e8 bf16-rounded products: compare relative to the mass of the terms
+        mass_v = (x["d_o"][:, hs].double().abs() * res["o"][:, hs].double().abs()).sum().item()
+        mass_k = (res["dq"][:, hs].double().abs() * x["q"][:, hs].double().abs()).sum().item()
+        assert abs(lhs_v - rhs_v) <= 5e-3 * mass_v, (g, lhs_v, rhs_v, mass_v)
+        assert abs(lhs_k - rhs_k) <= 5e-3 * mass_k, (g, lhs_k, rhs_k, mass_k)
+
+
+def _untouched(w, x, res, osel, ocnt, pt):
+    for g in range(w.Hkv):
+        pages = np.arange(w.n) if osel is None else osel[g][:ocnt[g]]
+        untouched = np.setdiff1d(np.arange(w.n_phys), pt[pages])
+        if len(untouched):
+            idx = torch.as_tensor(untouched, device=res["dk_pool"].device)
+            assert not res["dk_pool"][idx, g].any() and not res["dv_pool"][idx, g].any()
+
+
+@pytest.mark.parametrize("name", ["qwen_sparse_256k", "qwen_sparse_1m"])
+def test_sparse_full_size(name):
+    w = WORKLOADS[name]
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    sel, cnt, scores, res = _run_gpu(w, x)
+    osel, ocnt, oscores = pu.oracle_select(w, hx)
+    assert np.array_equal(scores.cpu().numpy().view(np.uint32), oscores.view(np.uint32)), "scores differ"
+    assert np.array_equal(cnt.cpu().numpy(), ocnt) and np.array_equal(sel.cpu().numpy(), osel)
+    # the boosted pages must show up in the selection of the heads whose pooled query points their way
+    boosted = set(x["boosted"].cpu().numpy().tolist())
+    hit = [len(boosted & set(osel[g][:w.top_k].tolist())) for g in range(w.Hkv)]
+    assert max(hit) >= min(len(boosted), w.top_k) * 0.9, hit
+    _check_rows(w, hx, res, osel, ocnt, _sample_rows(w, 160, 1))
+    g = 1
+    pages = [int(osel[g][0]), int(osel[g][w.top_k // 2]), int(osel[g][w.top_k]), int(osel[g][w.top_k + w.m // 2]),
+             int(osel[g][ocnt[g] - 1])]   # past pages, first / middle / last local (diagonal) page
+    _check_units(w, hx, res, osel, ocnt, g, pages)
+    _check_identities(w, x, res)
+    _untouched(w, x, res, osel, ocnt, hx["page_table"])
+
+
+def test_dense_full_size():
+    w = WORKLOADS["qwen_dense_64k"]
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    _, _, _, res = _run_gpu(w, x)
+    _check_rows(w, hx, res, None, None, _sample_rows(w, 96, 2))
+    _check_identities(w, x, res)
+
+
+def test_stress_4m_history():
+    """4M-token history, chunk 8192, top-k 256, bf16 gradient pool: selection in full, sampled rows, identities."""
+    w = WORKLOADS["qwen_sparse_4m"]
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * 2**30:
+        pytest.skip("needs ~40 GiB of free HBM")
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    sel, cnt, scores, res = _run_gpu(w, x)
+    osel, ocnt, oscores = pu.oracle_select(w, hx)
+    assert np.array_equal(scores.cpu().numpy().view(np.uint32), oscores.view(np.uint32)), "scores differ"
+    assert np.array_equal(cnt.cpu().numpy(), ocnt) and np.array_equal(sel.cpu().numpy(), osel)
+    _check_rows(w, hx, res, osel, ocnt, _sample_rows(w, 64, 3))
+    _check_identities(w, x, res)
+    _untouched(w, x, res, osel, ocnt, hx["page_table"])
