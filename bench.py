@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--workload", default="qwen_sparse_1m")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -113,6 +115,13 @@ def main():
                            x["dk_pool"], x["dv_pool"], sl, ct, dq, ws_bw)
         return N
 
+    if args.calibrate_copy:
+        # an elementwise kernel (not a DMA copy) that reads 1 GiB and writes 1 GiB
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
@@ -156,6 +165,14 @@ def main():
         ach = by / (avg_ms * 1e-3) / 1e9
         roof = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_ms": avg_ms, "launches": launches}
+    # HBM traffic of the dominant kernel (bytes per launch, read + write) from the committed
+    # FETCH_SIZE / WRITE_SIZE profile of this workload, if there is one
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 5 and f[0] == name and f[1] == "read_bytes" and f[3] == "write_bytes":
+                roof["traffic"] = int(f[2]) + int(f[4])
     kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof.items()}
     if "page_score" in kernels:
         by = sum((desc_at(s)[0] // w.P - w.m) for s in range(args.steps)) / args.steps * w.P * w.D * 2 * w.Hkv
