@@ -8,17 +8,16 @@
 // group and a workgroup's rows span at most three token blocks (short causal
 // diagonal).  Each wave keeps its 32 query rows (as the B operand of
 // S^T = K Q^T) and its 32 x 128 output block in registers.  Pages are processed
-// as two half tiles of 64 keys: K as a natural half tile (direct global -> LDS
-// loads, double buffered), V as a transposed half tile (triple buffered).  In
+// as two half tiles of 64 keys: K as a natural half tile, V as a transposed half
+// tile, both double buffered and staged through registers.  In
 // the S^T layout every lane owns one query row, so the online-softmax
 // statistics are per-lane scalars.
 //
 // Schedule (one barrier per half tile t): S_t = K_t Q^T, online softmax, then
 // O += V_t P_t.  LDS operand fragments are fetched in batches of four, one batch
-// ahead of the matrix instructions that use them.  The two waves that share a
-// SIMD (w and w + 4) place the O += V P product at opposite ends of the
-// iteration (waves 0-3 right after their softmax, waves 4-7 at the top of the
-// next iteration), so one wave's matrix work overlaps the other wave's vector work.
+// ahead of the matrix instructions that use them; the next half tile is fetched
+// from global memory into registers at the top of an iteration and written to
+// the other LDS buffer at its bottom.
 #include "mfma_common.h"
 
 namespace oomb {
@@ -28,14 +27,13 @@ constexpr int FW_THREADS = FW_WAVES * 64;
 constexpr int FW_ROWS = FW_WAVES * 32;
 constexpr int HT = 64;                    // keys per half tile
 constexpr int HT_BYTES = HT * HD * 2;     // 16 KiB
-constexpr int FW_LDS = 5 * HT_BYTES;      // K0 K1 V0 V1 V2
+constexpr int FW_LDS = 4 * HT_BYTES;      // K0 K1 V0 V1
 
 __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2;  // waves w and w + 4 share a SIMD
-
+  
   // workgroup -> (KV head, row tile).  Workgroups are dealt round-robin to the 8
   // XCDs; keeping a KV head on a fixed set of XCDs lets its pages stay in that L2.
   int g, tile;
@@ -110,29 +108,39 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
     return (int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
            (int64_t)(ht & 1) * HT * p.pool_tok_stride;
   };
-  // this wave's share of a K half tile: 8 rows, two 1 KiB chunks, straight into LDS
-  auto load_k = [&](int32_t ht, unsigned char* dst) {
-    const bf16_t* base = (const bf16_t*)p.k_pool + ht_off(ht) + (int64_t)(8 * wave) * p.pool_tok_stride;
-    const uint32_t ts_bytes = (uint32_t)p.pool_tok_stride * 2u;
+  // this wave's share of a K half tile: 8 rows = two 4-row chunks, staged through registers
+  // (a direct global -> LDS load makes the compiler wait for it before the next LDS read,
+  // which exposes the whole memory latency every iteration).  Lane l of a chunk lands at
+  // granule position l % 16 of row l / 16, so it fetches the granule the swizzle maps there.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 kr0, kr1;
+  uint32_t knat_off[2];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const uint32_t lrow = 4 * x + (lane >> 4);
-      const uint32_t cc = (lane & 15) ^ ((8 * wave + lrow) & 15);
-      const char* src = reinterpret_cast<const char*>(base) + (lrow * ts_bytes + cc * 16u);
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(dst + (8 * wave + 4 * x) * 256), 16, 0, 0);
-    }
+  for (int x = 0; x < 2; ++x) {
+    const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
+    knat_off[x] = srow * ((uint32_t)p.pool_tok_stride * 2u) + (((lane & 15) ^ (srow & 15)) << 4);
+  }
+  auto load_k = [&](int32_t ht) {
+    const char* base = reinterpret_cast<const char*>((const bf16_t*)p.k_pool + ht_off(ht));
+    kr0 = *reinterpret_cast<const u32x4*>(base + knat_off[0]);
+    kr1 = *reinterpret_cast<const u32x4*>(base + knat_off[1]);
+  };
+  auto store_k = [&](unsigned char* dst) {
+    *reinterpret_cast<u32x4*>(dst + (8 * wave) * 256 + lane * 16) = kr0;
+    *reinterpret_cast<u32x4*>(dst + (8 * wave + 4) * 256 + lane * 16) = kr1;
   };
   // this wave's octet (index = wave) of a V half tile: tokens 16u + 4h2 + {0..3, 8..11}
-  uint32_t vr[8];
-  auto load_v = [&](int32_t ht) {
-    const bf16_t* base = (const bf16_t*)p.v_pool + ht_off(ht);
+  uint32_t vr[8], vro[8];
+  {
     const int u = wave >> 1, h2 = wave & 1;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = 16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2);
-      vr[e] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(base + (int64_t)tok * p.pool_tok_stride) +
-                                                 (uint32_t)lane * 4u);
-    }
+    for (int e = 0; e < 8; ++e)
+      vro[e] = (uint32_t)(16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2)) * ((uint32_t)p.pool_tok_stride * 2u) + (uint32_t)lane * 4u;
+  }
+  auto load_v = [&](int32_t ht) {
+    const char* base = reinterpret_cast<const char*>((const bf16_t*)p.v_pool + ht_off(ht));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vr[e] = *reinterpret_cast<const uint32_t*>(base + vro[e]);
   };
   auto store_v = [&](unsigned char* dst) {
     uint4 lo, hi;
@@ -206,18 +214,16 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
     for (int u = 0; u < 4; ++u) of[3] = mfma32(as_bf16x8(fb[u]), pf[u], of[3]);
     __builtin_amdgcn_sched_barrier(0);
   };
-  // causal mask of a diagonal half tile (first token `first`) + row maximum, merged with
-  // the running maximum.  Done as soon as a half tile's S is complete, one iteration
-  // before its exponentials, so that the exponentials never wait for a reduction.
-  auto mask_and_max = [&](f32x16* sv, int64_t first) -> float {
-    if (first + HT - 1 > a_wave_min) {
-      const int rel = (int)(a_i - first) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
+  // causal mask of a diagonal half tile (first token `first`)
+  auto mask_diag = [&](f32x16* sv, int64_t first) {
+    const int rel = (int)(a_i - first) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
+    for (int kb2 = 0; kb2 < 2; ++kb2)
 #pragma unroll
-        for (int x = 0; x < 16; ++x)
-          if (32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) sv[kb2][x] = -INFINITY;
-    }
+      for (int x = 0; x < 16; ++x)
+        if (32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) sv[kb2][x] = -INFINITY;
+  };
+  auto row_max = [&](const f32x16* sv) -> float {
     float mx = sv[0][0];
 #pragma unroll
     for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -266,40 +272,53 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 
   // prologue: K_0 and V_0 into LDS
   if (T2 > 0) {
-    load_k(0, kbuf);
+    load_k(0);
     load_v(0);
+    store_k(kbuf);
     store_v(vbuf);
   }
-  wait_vmem();
   __syncthreads();
-  bool act_prev = false;  // did this wave compute P for half tile t - 1
-
-  for (int32_t t = 0; t < T2; ++t) {
+  // Half tiles [0, T_full) are seen in full by every row of the workgroup: their loop body is
+  // straight-line code with no masking and no per-wave conditions.  The remaining (diagonal)
+  // half tiles run the general body.  V buffers alternate like the K buffers.
+  int32_t T_full = 0;
+  {
+    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)(tile * (FW_ROWS / 32)));
+    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, g, (a_blk_min - (TP - 1)) / TP, lane);
+    if (T_full > T2) T_full = T2;
+  }
+  auto iteration = [&](const int32_t t, const bool general) {
     pw.advance(p, g, T, t >> 1, lane);
-    // tiles for the next iteration: K_{t+1} into the other K buffer, V_{t+1} into the third V buffer
     const bool more = t + 1 < T2;
     if (more) {
-      load_k(t + 1, kbuf + ((t + 1) & 1) * HT_BYTES);
+      load_k(t + 1);
       load_v(t + 1);
     }
-    if (grp == 1 && act_prev) pv(vbuf + ((t + 2) % 3) * HT_BYTES);  // waves 4-7: product of half tile t - 1
-
-    const int64_t first = ht_first(t);
-    const bool act = first <= a_wave_max;  // some row of this wave sees the half tile
-    if (act) {
-      qk(sc, kbuf + (t & 1) * HT_BYTES);
-      const float m_tile = mask_and_max(sc, first);
-      rescale(m_tile);
+    const unsigned char* kt = kbuf + (t & 1) * HT_BYTES;
+    const unsigned char* vt = vbuf + (t & 1) * HT_BYTES;
+    if (!general) {
+      qk(sc, kt);
+      rescale(row_max(sc));
       l_run += exps();
-      if (grp == 0) pv(vbuf + (t % 3) * HT_BYTES);  // waves 0-3: product of this half tile
+      pv(vt);
+    } else {
+      const int64_t first = ht_first(t);
+      if (first <= a_wave_max) {  // wave-uniform: some row of this wave sees the half tile
+        qk(sc, kt);
+        if (first + HT - 1 > a_wave_min) mask_diag(sc, first);
+        rescale(row_max(sc));
+        l_run += exps();
+        pv(vt);
+      }
     }
-    act_prev = act;
-
-    if (more) store_v(vbuf + ((t + 1) % 3) * HT_BYTES);
-    wait_vmem();
+    if (more) {
+      store_k(kbuf + ((t + 1) & 1) * HT_BYTES);
+      store_v(vbuf + ((t + 1) & 1) * HT_BYTES);
+    }
     __syncthreads();
-  }
-  if (grp == 1 && act_prev) pv(vbuf + ((T2 - 1) % 3) * HT_BYTES);
+  };
+  for (int32_t t = 0; t < T_full; ++t) iteration(t, false);
+  for (int32_t t = T_full; t < T2; ++t) iteration(t, true);
 
   // epilogue: O = acc / l, LSE = ln(2) * (m * c + log2 l)
   const float l_tot = half_sum(l_run);
