@@ -27,7 +27,7 @@ constexpr int FW_THREADS = FW_WAVES * 64;
 constexpr int FW_ROWS = FW_WAVES * 32;
 constexpr int HT = 64;                    // keys per half tile
 constexpr int HT_BYTES = HT * HD * 2;     // 16 KiB
-constexpr int FW_LDS = 4 * HT_BYTES;      // K0 K1 V0 V1
+constexpr int FW_LDS = 6 * HT_BYTES;      // K0 K1 K2 V0 V1 V2
 
 __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -75,32 +75,36 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + 16 * kk + 8 * hh));
 
-  f32x16 of[4], sc[2];
-  bf16x8 pf[4];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  f32x16 of[4], sA, sB;   // output block; scores of the two units in flight
+  u32x4 pA[2], pB[2];     // bf16 probabilities of the two units in flight (B operands of V^T P^T)
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int x = 0; x < 16; ++x) of[db][x] = 0.f;
 #pragma unroll
-  for (int u = 0; u < 4; ++u) pf[u] = as_bf16x8(make_uint4(0, 0, 0, 0));
-  float m_run = -1e30f, l_run = 0.f;
+  for (int u = 0; u < 2; ++u) { pA[u] = (u32x4){0u, 0u, 0u, 0u}; pB[u] = (u32x4){0u, 0u, 0u, 0u}; }
+  float m_run = -1e30f, l_run = 0.f, alpha_pend = 1.f;
   const float c = p.sm_scale * 1.4426950408889634f;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   // LDS operand addresses.  The swizzles XOR a per-lane constant into the granule
   // index, so an operand address is (lane base ^ small constant) + block offset; the
   // block offset goes into the instruction's immediate field.
+  // LDS: V buffers at 0, 16K, 32K; K buffers at 48K, 64K, 80K.  The K addresses carry the 48K in the
+  // register so that every immediate offset stays below 64K.
+  constexpr int KB = 3 * HT_BYTES;
   uint32_t ka[8], va[4];
   {
     const uint32_t kbase = lq * 256 + (((lq & 15) ^ hh) << 4);           // natural, 16 granules per row
     const uint32_t vbase = lq * 128 + ((((lq >> 1) & 7) ^ hh) << 4);     // transposed, 8 granules per row
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ka[j] = kbase ^ (j << 5);
+    for (int j = 0; j < 8; ++j) ka[j] = (kbase ^ (j << 5)) + KB;  // K buffers sit above the V buffers
 #pragma unroll
     for (int j = 0; j < 4; ++j) va[j] = vbase ^ (j << 5);
   }
-  unsigned char* const kbuf = smem;
-  unsigned char* const vbuf = smem + 2 * HT_BYTES;
+  unsigned char* const kbuf = smem + KB;
+  unsigned char* const vbuf = smem;
 
   // half tile ht: page j = ht / 2, keys 64 (ht % 2) .. + 63 of it
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * HT; };
@@ -112,7 +116,6 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   // (a direct global -> LDS load makes the compiler wait for it before the next LDS read,
   // which exposes the whole memory latency every iteration).  Lane l of a chunk lands at
   // granule position l % 16 of row l / 16, so it fetches the granule the swizzle maps there.
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4 kr0, kr1;
   uint32_t knat_off[2];
 #pragma unroll
@@ -156,169 +159,200 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
     *reinterpret_cast<uint4*>(dst + (d0 * 8 + (wave ^ ((d0 >> 1) & 7))) * 16) = lo;
     *reinterpret_cast<uint4*>(dst + (d1 * 8 + (wave ^ ((d1 >> 1) & 7))) * 16) = hi;
   };
-  // S^T (64 keys x 32 queries) = K Q^T; fragments fetched one batch of four ahead
-  auto qk = [&](f32x16* dst, const unsigned char* kt) {
-    uint4 fa[4], fb[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fa[j] = *reinterpret_cast<const uint4*>(kt + ka[j]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const uint4*>(kt + ka[4 + j]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int x = 0; x < 16; ++x) { dst[0][x] = 0.f; dst[1][x] = 0.f; }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dst[0] = mfma32(as_bf16x8(fa[j]), qf[j], dst[0]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fa[j] = *reinterpret_cast<const uint4*>(kt + ka[j] + 8192);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dst[0] = mfma32(as_bf16x8(fb[j]), qf[4 + j], dst[0]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const uint4*>(kt + ka[4 + j] + 8192);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dst[1] = mfma32(as_bf16x8(fa[j]), qf[j], dst[1]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dst[1] = mfma32(as_bf16x8(fb[j]), qf[4 + j], dst[1]);
-    __builtin_amdgcn_sched_barrier(0);
+
+  // ---- the software pipeline -------------------------------------------------------
+  // A unit is 32 keys (half of a half tile).  One step of the pipeline runs three
+  // mutually independent instruction streams, so matrix and vector instructions of one
+  // wave overlap whatever the other wave of the SIMD is doing:
+  //   matrix: O += V_u P_u (8 MFMA) interleaved with S_{u+2} = K_{u+2} Q^T (8 MFMA)
+  //   vector: online softmax of S_{u+1} -> P_{u+1}, row sum, pending rescale factor
+  //   LDS:    operand fragments, one batch of four ahead (the last batch of a step
+  //           fetches the first batch of the next step)
+  // The step is written as 16 slots of one MFMA + one fragment read + one slice of the
+  // softmax; sched_barrier keeps the slots in source order.
+  u32x4 fr[8];  // two batches of four fragments
+  float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f, t4 = 0.f, rs = 0.f, mc = 0.f, alpha_new = 1.f;
+
+  // fragment e of batch b: e = 0, 2 -> K rows of k-steps 2b, 2b+1; e = 1, 3 -> V^T rows of dim block b.
+  // ko / vo are compile-time byte offsets of the K unit and the V half tile in LDS, so every address
+  // is a loop-invariant register plus an immediate
+  auto frag = [&](const int ko, const int vo, int v, int b, int e) __attribute__((always_inline)) -> u32x4 {
+    if ((e & 1) == 0) return *reinterpret_cast<const u32x4*>(smem + (ka[2 * b + (e >> 1)] + ko));
+    return *reinterpret_cast<const u32x4*>(smem + (va[2 * v + (e >> 1)] + (vo + 4096 * b)));
   };
-  // O^T (128 dims x 32 queries) += V^T P^T
-  auto pv = [&](const unsigned char* vt) {
-    uint4 fa[4], fb[4];
+  // slice sl of the softmax of one unit: scores s (C layout: register x = key 8 (x / 4) + 4 hh + x % 4)
+  // -> bf16 probabilities pr; rel = largest visible key index of this lane's row, less 4 hh
+  auto sm_slice = [&](const int sl, f32x16& s, u32x4* pr, const int rel, const bool general) __attribute__((always_inline)) {
+    if (sl == 0) {
+      if (general) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(vt + va[u]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 4096);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) of[0] = mfma32(as_bf16x8(fa[u]), pf[u], of[0]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 2 * 4096);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) of[1] = mfma32(as_bf16x8(fb[u]), pf[u], of[1]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(vt + va[u] + 3 * 4096);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) of[2] = mfma32(as_bf16x8(fa[u]), pf[u], of[2]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) of[3] = mfma32(as_bf16x8(fb[u]), pf[u], of[3]);
-    __builtin_amdgcn_sched_barrier(0);
+        for (int x = 0; x < 16; ++x)
+          if (8 * (x >> 2) + (x & 3) > rel) s[x] = -INFINITY;
+      }
+      t0 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+      t1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+    } else if (sl == 1) {
+      t2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+      t3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+      t4 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+    } else if (sl == 2) {
+      t0 = fmaxf(fmaxf(t0, t1), t2);
+      t3 = fmaxf(fmaxf(t3, t4), s[15]);
+      t0 = half_max(fmaxf(t0, t3));
+    } else if (sl == 3) {
+      const float m_new = fmaxf(m_run, t0);
+      alpha_new = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      m_run = m_new;
+      mc = m_new * c;
+      rs = 0.f;
+    } else if (sl < 12) {
+      const int x = 2 * (sl - 4);
+      s[x] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -mc));
+      s[x + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x + 1], c, -mc));
+    } else {
+      const int q = sl - 12;
+      const uint32_t w0 = pack2_bf16(s[4 * q + 0], s[4 * q + 1]);
+      const uint32_t w1 = pack2_bf16(s[4 * q + 2], s[4 * q + 3]);
+      rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w0), ones, rs, false);
+      rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w1), ones, rs, false);
+      pr[q >> 1][2 * (q & 1) + 0] = w0;
+      pr[q >> 1][2 * (q & 1) + 1] = w1;
+      if (sl == 15) {
+        l_run = __builtin_fmaf(l_run, alpha_new, rs);
+        alpha_pend = alpha_new;
+      }
+    }
   };
-  // causal mask of a diagonal half tile (first token `first`)
-  auto mask_diag = [&](f32x16* sv, int64_t first) {
-    const int rel = (int)(a_i - first) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
-#pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-      for (int x = 0; x < 16; ++x)
-        if (32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) sv[kb2][x] = -INFINITY;
-  };
-  auto row_max = [&](const f32x16* sv) -> float {
-    float mx = sv[0][0];
-#pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-      for (int x = 0; x < 16; ++x) mx = fmaxf(mx, sv[kb2][x]);
-    return half_max(mx);
-  };
-  // m_run <- max(m_run, m_tile); O and l are rescaled only when some row's maximum moved
-  auto rescale = [&](float m_tile) {
-    const float m_new = fmaxf(m_run, m_tile);
-    if (__any(m_new != m_run)) {  // wave-uniform
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-      l_run *= alpha;
+  // one pipeline step.  v = which half of the half tiles (K rows 32 v .., V token groups 2 v, 2 v + 1);
+  // (ko, vo) = LDS offsets of this step's operands, (kn, vn) = those of the next step (which has v ^ 1)
+  auto step = [&](const int v, const int ko, const int vo, const int kn, const int vn, f32x16& s_in, u32x4* p_out,
+                  const u32x4* p_in, f32x16& s_out, const int rel, const bool general) __attribute__((always_inline)) {
+    // rescale left pending by the previous softmax: O and l are multiplied only when some row's maximum moved
+    if (__any(alpha_pend != 1.f)) {  // wave-uniform
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int x = 0; x < 16; ++x) of[db][x] *= alpha;
-      m_run = m_new;
+        for (int x = 0; x < 16; ++x) of[db][x] *= alpha_pend;
     }
-  };
-  // P = exp2(c S - c m_run) of the half tile in sc, rounded to bf16 into pf; returns the
-  // row sum of the rounded probabilities (what the PV product uses)
-  auto exps = [&]() -> float {
-    const float mc = m_run * c;
-    float rs = 0.f;
 #pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2) {
+    for (int x = 0; x < 16; ++x) s_out[x] = 0.f;
 #pragma unroll
-      for (int x = 0; x < 16; ++x) sc[kb2][x] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb2][x], c, -mc));
+    for (int sl = 0; sl < 16; ++sl) {
+      const int b = sl >> 2, q = sl & 3;
+      const int cur = 4 * (b & 1), nxt = 4 - cur;
+      if (q == 0) {  // the whole next batch at once: one wait per batch instead of one per fragment
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        uint4 w;
-        w.x = pack2_bf16(sc[kb2][8 * u + 0], sc[kb2][8 * u + 1]);
-        w.y = pack2_bf16(sc[kb2][8 * u + 2], sc[kb2][8 * u + 3]);
-        w.z = pack2_bf16(sc[kb2][8 * u + 4], sc[kb2][8 * u + 5]);
-        w.w = pack2_bf16(sc[kb2][8 * u + 6], sc[kb2][8 * u + 7]);
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), ones, rs, false);
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), ones, rs, false);
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), ones, rs, false);
-        rs = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), ones, rs, false);
-        pf[2 * kb2 + u] = as_bf16x8(w);
+        for (int e = 0; e < 4; ++e) fr[nxt + e] = b < 3 ? frag(ko, vo, v, b + 1, e) : frag(kn, vn, v ^ 1, 0, e);
+        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): the batch fetched one batch ago has arrived
       }
+      if (q == 0) s_out = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 0]), qf[2 * b], s_out);
+      if (q == 1) of[b] = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 1]), __builtin_bit_cast(bf16x8, p_in[0]), of[b]);
+      if (q == 2) s_out = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 2]), qf[2 * b + 1], s_out);
+      if (q == 3) of[b] = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 3]), __builtin_bit_cast(bf16x8, p_in[1]), of[b]);
+      sm_slice(sl, s_in, p_out, rel, general);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    return rs;
+    // keep this step's softmax in this step: without a use here the compiler sinks it into the
+    // block of the next step, in front of that step's first matrix instruction
+    asm volatile("" : "+v"(p_out[0]), "+v"(p_out[1]), "+v"(l_run), "+v"(alpha_pend));
   };
+  // unpipelined S = K Q^T of one unit (prologue only)
+  auto qk_plain = [&](f32x16& dst, const int ko) __attribute__((always_inline)) {
+#pragma unroll
+    for (int x = 0; x < 16; ++x) dst[x] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      dst = mfma32(__builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(smem + (ka[j] + ko))), qf[j], dst);
+  };
+  auto rel_of = [&](int64_t first) -> int { return (int)(a_i - first) - 4 * hh; };
 
-  // prologue: K_0 and V_0 into LDS
-  if (T2 > 0) {
-    load_k(0);
-    load_v(0);
-    store_k(kbuf);
-    store_v(vbuf);
-  }
-  __syncthreads();
-  // Half tiles [0, T_full) are seen in full by every row of the workgroup: their loop body is
-  // straight-line code with no masking and no per-wave conditions.  The remaining (diagonal)
-  // half tiles run the general body.  V buffers alternate like the K buffers.
+  // Half tiles [0, T_full) are seen in full by every row of the workgroup; steps whose
+  // softmax unit lies in them need no mask.
   int32_t T_full = 0;
   {
     const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)(tile * (FW_ROWS / 32)));
     if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, g, (a_blk_min - (TP - 1)) / TP, lane);
     if (T_full > T2) T_full = T2;
   }
-  auto iteration = [&](const int32_t t, const bool general) {
+
+  // prologue: K_0, K_1, V_0 into LDS; K_2 and V_1 into the staging registers; S_0, S_1, P_0
+  if (T2 > 0) {
+    load_k(0);
+    load_v(0);
+    store_k(kbuf);
+    store_v(vbuf);
+  }
+  if (T2 > 1) {
+    load_k(1);
+    store_k(kbuf + HT_BYTES);
+    load_v(1);
+  }
+  if (T2 > 2) load_k(2);
+  __syncthreads();
+  if (T2 > 0) {
+    qk_plain(sA, 0);
+    qk_plain(sB, 8192);
+    const int rel0 = rel_of(ht_first(0));
+#pragma unroll
+    for (int sl = 0; sl < 16; ++sl) sm_slice(sl, sA, pA, rel0, true);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) fr[q] = frag(HT_BYTES, 0, 0, 0, q);
+  }
+  // pool offset of the page that holds half tile t + 3 (K) at the top of step B of iteration t; the page
+  // of half tile t + 2 (V) is the same one for even t and the previous one for odd t
+  auto page_off = [&](int32_t j) -> int64_t {
+    return (int64_t)pw.phys(j) * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
+  };
+  int64_t off_k = page_off(T > 1 ? 1 : 0);
+  const int64_t half_off = (int64_t)HT * p.pool_tok_stride;
+
+  // iteration t (r = t mod 3): steps A (units 2t | 2t+1 | 2t+2) and B (2t+1 | 2t+2 | 2t+3); K_{t+1}
+  // (buffer r+1) and V_t (buffer r) are read, K_{t+2} (buffer r+2) and V_{t+1} (buffer r+1) are written
+  // before the barrier between A and B.  Three buffers each: a wave still in step B of the previous
+  // iteration reads K_t and V_{t-1}.  The loops are unrolled by three so that r is a constant.
+  auto iteration = [&](const int32_t t, const int r, const bool general) __attribute__((always_inline)) {
+    const int kc = ((r + 1) % 3) * HT_BYTES, kw = ((r + 2) % 3) * HT_BYTES;
+    const int vc = r * HT_BYTES, vw = ((r + 1) % 3) * HT_BYTES;
     pw.advance(p, g, T, t >> 1, lane);
-    const bool more = t + 1 < T2;
-    if (more) {
-      load_k(t + 1);
-      load_v(t + 1);
+    int relA = 0, relB = 0;
+    if (general) {
+      relA = rel_of(ht_first(t) + 32);
+      relB = t + 1 < T2 ? rel_of(ht_first(t + 1)) : -1;
     }
-    const unsigned char* kt = kbuf + (t & 1) * HT_BYTES;
-    const unsigned char* vt = vbuf + (t & 1) * HT_BYTES;
-    if (!general) {
-      qk(sc, kt);
-      rescale(row_max(sc));
-      l_run += exps();
-      pv(vt);
-    } else {
-      const int64_t first = ht_first(t);
-      if (first <= a_wave_max) {  // wave-uniform: some row of this wave sees the half tile
-        qk(sc, kt);
-        if (first + HT - 1 > a_wave_min) mask_diag(sc, first);
-        rescale(row_max(sc));
-        l_run += exps();
-        pv(vt);
+    step(0, kc, vc, kc + 8192, vc, sB, pB, pA, sA, relA, general);
+    if (t + 2 < T2) store_k(kbuf + kw);
+    if (t + 1 < T2) store_v(smem + vw);
+    __syncthreads();
+    {
+      const int64_t off_v = off_k;
+      if ((t & 1) && t + 3 < T2) off_k = page_off((t + 3) >> 1);
+      if (t + 3 < T2) {
+        const char* base = reinterpret_cast<const char*>((const bf16_t*)p.k_pool + off_k + ((t + 3) & 1) * half_off);
+        kr0 = *reinterpret_cast<const u32x4*>(base + knat_off[0]);
+        kr1 = *reinterpret_cast<const u32x4*>(base + knat_off[1]);
+      }
+      if (t + 2 < T2) {
+        const char* base = reinterpret_cast<const char*>((const bf16_t*)p.v_pool + off_v + ((t + 2) & 1) * half_off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vr[e] = *reinterpret_cast<const uint32_t*>(base + vro[e]);
       }
     }
-    if (more) {
-      store_k(kbuf + ((t + 1) & 1) * HT_BYTES);
-      store_v(vbuf + ((t + 1) & 1) * HT_BYTES);
-    }
-    __syncthreads();
+    step(1, kc + 8192, vc, kw, vw, sA, pA, pB, sB, relB, general);
   };
-  for (int32_t t = 0; t < T_full; ++t) iteration(t, false);
-  for (int32_t t = T_full; t < T2; ++t) iteration(t, true);
+  {
+    int32_t t = 0;
+    for (; t + 3 < T_full; t += 3) {
+      iteration(t, 0, false);
+      iteration(t + 1, 1, false);
+      iteration(t + 2, 2, false);
+    }
+    for (; t < T2; t += 3) {
+      iteration(t, 0, true);
+      if (t + 1 < T2) iteration(t + 1, 1, true);
+      if (t + 2 < T2) iteration(t + 2, 2, true);
+    }
+  }
+  // the last softmax (a fully masked unit) leaves alpha_pend = 1: nothing is pending here
 
   // epilogue: O = acc / l, LSE = ln(2) * (m * c + log2 l)
   const float l_tot = half_sum(l_run);
