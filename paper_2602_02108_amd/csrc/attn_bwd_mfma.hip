@@ -90,10 +90,15 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restri
 // dQ.  LDS: two stages of {K natural half tile, V natural half tile, K transposed
 // half tile}, 16 KiB each.  One barrier per half tile of 64 keys; the next half tile
 // is fetched into registers at the top of an iteration and written to the other
-// stage at its bottom.
-constexpr int DQ_STAGE = 3 * 16384;
-constexpr int DQ_LDS = 2 * DQ_STAGE;
+// stage at its bottom.  The natural tiles of both stages sit in the lower 64 KiB and
+// the transposed tiles above them, so that every operand address is a loop-invariant
+// register plus an immediate offset.
+constexpr int DQ_LDS = 6 * 16384;
+constexpr int DQ_KT = 4 * 16384;  // first transposed tile
 
+// CONTIG: the tokens of a page are contiguous (pool_tok_stride == head dim), which turns the row
+// offsets of the staging loads into immediates.
+template <bool CONTIG>
 __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const float* __restrict__ delta_rs,
                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
                                                             int tiles_per_head, int xcd_map) {
@@ -133,6 +138,13 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   pw.init(p, g, T, lane);
   int32_t T2 = 2 * T;
   if (T > 0 && (int64_t)list_at(p, g, T - 1) * TP + 64 > a_blk_max) T2 -= 1;  // second half of the last page unseen
+  // half tiles [0, T_full) are seen in full by every row of the workgroup
+  int32_t T_full = 0;
+  {
+    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)(tile * (DQ_ROWS / 32)));
+    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, g, (a_blk_min - (TP - 1)) / TP, lane);
+    if (T_full > T2) T_full = T2;
+  }
 
   const int64_t roff = (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
   bf16x8 qf[8], dof[8];
@@ -159,18 +171,14 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
 #pragma unroll
     for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) ta[k] = tbase ^ (k << 5);
+    for (int k = 0; k < 4; ++k) ta[k] = (tbase ^ (k << 5)) + DQ_KT;
   }
 
-  // half tile ht: page ht / 2, keys 64 (ht % 2) .. + 63
-  auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
-  auto ht_off = [&](int32_t ht) -> int64_t {
-    return (int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
-           (int64_t)(ht & 1) * 64 * p.pool_tok_stride;
-  };
   // staging registers: this wave's 8 rows of the natural K and V half tiles (two 4-row
   // chunks each, source granule pre-swizzled) and its octet of the transposed K half tile
-  const uint32_t ts_bytes = (uint32_t)p.pool_tok_stride * 2u;
+  const uint32_t ts_bytes = CONTIG ? (uint32_t)(HD * 2) : (uint32_t)p.pool_tok_stride * 2u;
+  // rows 8 wave + (lane / 16) and + 4 of the natural tiles: the swizzle (row & 15) only differs in
+  // bit 2 between the two, so the second offset is the first with that granule bit flipped
   uint32_t nat_off[2];
 #pragma unroll
   for (int x = 0; x < 2; ++x) {
@@ -179,113 +187,146 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   }
   u32x4 kn0, kn1, vn0, vn1;
   uint32_t kt[8];
-  auto load_stage = [&](int32_t ht) {
-    const int64_t off = ht_off(ht) * 2;
+  // byte offset of half tile ht (page ht / 2, keys 64 (ht % 2) .. + 63) in the pools
+  auto ht_off = [&](int32_t ht) -> int64_t {
+    return ((int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
+            (int64_t)(ht & 1) * 64 * p.pool_tok_stride) * 2;
+  };
+  auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
+  // The empty asm keeps each 32-bit lane offset opaque, so that the loads use the
+  // (scalar base + 32-bit lane offset) addressing form instead of 64-bit lane addresses.
+  const uint32_t kt_lane = (uint32_t)(16 * (wave >> 1) + 4 * (wave & 1)) * ts_bytes + (uint32_t)lane * 4u;
+  auto load_stage = [&](const int64_t off) __attribute__((always_inline)) {
     const char* kb = reinterpret_cast<const char*>(p.k_pool) + off;
     const char* vb = reinterpret_cast<const char*>(p.v_pool) + off;
-    kn0 = *reinterpret_cast<const u32x4*>(kb + nat_off[0]);
-    vn0 = *reinterpret_cast<const u32x4*>(vb + nat_off[0]);
-    kn1 = *reinterpret_cast<const u32x4*>(kb + nat_off[1]);
-    vn1 = *reinterpret_cast<const u32x4*>(vb + nat_off[1]);
-    const int u = wave >> 1, h2 = wave & 1;
+    uint32_t o0 = nat_off[0], o1 = nat_off[1], ol = kt_lane;
+    asm volatile("" : "+v"(o0), "+v"(o1), "+v"(ol));
+    kn0 = *reinterpret_cast<const u32x4*>(kb + o0);
+    vn0 = *reinterpret_cast<const u32x4*>(vb + o0);
+    kn1 = *reinterpret_cast<const u32x4*>(kb + o1);
+    vn1 = *reinterpret_cast<const u32x4*>(vb + o1);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const uint32_t ro = (uint32_t)(16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2)) * ts_bytes;  // wave-uniform
-      kt[e] = *reinterpret_cast<const uint32_t*>(kb + ro + (uint32_t)lane * 4u);
+      const char* kr = kb + (uint32_t)((e & 3) + 8 * (e >> 2)) * ts_bytes;  // uniform; an immediate when CONTIG
+      kt[e] = *reinterpret_cast<const uint32_t*>(kr + ol);
     }
   };
   const int tr_o0 = ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = ((2 * lane + 1) * 8 + (wave ^ (lane & 7))) * 16;
-  auto store_stage = [&](unsigned char* sb) {
-    *reinterpret_cast<u32x4*>(sb + (8 * wave) * 256 + lane * 16) = kn0;
-    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave) * 256 + lane * 16) = vn0;
-    *reinterpret_cast<u32x4*>(sb + (8 * wave + 4) * 256 + lane * 16) = kn1;
-    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave + 4) * 256 + lane * 16) = vn1;
-    *reinterpret_cast<uint4*>(sb + 32768 + tr_o0) = pack_hi_lo(kt, 0x05040100u);
-    *reinterpret_cast<uint4*>(sb + 32768 + tr_o1) = pack_hi_lo(kt, 0x07060302u);
+  auto store_stage = [&](const int st) __attribute__((always_inline)) {
+    unsigned char* nb = smem + st * 32768;
+    *reinterpret_cast<u32x4*>(nb + (8 * wave) * 256 + lane * 16) = kn0;
+    *reinterpret_cast<u32x4*>(nb + 16384 + (8 * wave) * 256 + lane * 16) = vn0;
+    *reinterpret_cast<u32x4*>(nb + (8 * wave + 4) * 256 + lane * 16) = kn1;
+    *reinterpret_cast<u32x4*>(nb + 16384 + (8 * wave + 4) * 256 + lane * 16) = vn1;
+    *reinterpret_cast<uint4*>(smem + DQ_KT + st * 16384 + tr_o0) = pack_hi_lo(kt, 0x05040100u);
+    *reinterpret_cast<uint4*>(smem + DQ_KT + st * 16384 + tr_o1) = pack_hi_lo(kt, 0x07060302u);
   };
 
-  // S^T, dP^T of one 32-key block kb2 of the half tile in sb; dS^T (bf16) into dsf[2 kb2 ..]
-  bf16x8 dsf[4];
-  auto block = [&](const unsigned char* sb, const int kb2, const bool diag, const int rel) {
+  // One half tile is 12 batches of four matrix instructions.  Per 32-key block kb2: four batches
+  // compute S^T and dP^T (fragments: K rows and V rows of k-steps 2b, 2b+1, used alternately so
+  // that neighbouring instructions are independent), the vector unit turns them into dS^T, and two
+  // batches add K^T dS^T of the block to dQ^T (dim blocks 0,1 then 2,3).  The fragments of a batch
+  // are fetched while the previous batch computes; one wait per batch.
+  u32x4 fr[8];
+  bf16x8 dsf[2];
+  auto fetch = [&](const int st, const int n, const int set) __attribute__((always_inline)) {
+    const int kb2 = n / 6, b = n % 6;
+    if (b < 4) {
+      const int o = st * 32768 + kb2 * 8192;
+      fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b] + o));
+      fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b] + (o + 16384)));
+      fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b + 1] + o));
+      fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b + 1] + (o + 16384)));
+    } else {
+      const int db = 2 * (b - 4), u = 2 * kb2;
+      const int o = st * 16384;
+      fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (ta[u] + (o + 4096 * db)));
+      fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (ta[u] + (o + 4096 * (db + 1))));
+      fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (ta[u + 1] + (o + 4096 * db)));
+      fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (ta[u + 1] + (o + 4096 * (db + 1))));
+    }
+  };
+  auto half_tile = [&](const int st, const bool general, const int rel) __attribute__((always_inline)) {
     f32x16 sv, dp;
-    uint4 fa[4], fb[4];
+    fetch(st, 0, 0);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[k] + kb2 * 8192);
+    for (int n = 0; n < 12; ++n) {
+      const int set = 4 * (n & 1);
+      const int kb2 = n / 6, b = n % 6;
+      if (n + 1 < 12) {
+        fetch(st, n + 1, 4 - set);
+        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): this batch has arrived
+        __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of this batch's matrix instructions
+      }
+      if (b < 4) {
+        if (b == 0) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[k] + kb2 * 8192);
-    __builtin_amdgcn_sched_barrier(0);
+          for (int x = 0; x < 16; ++x) { sv[x] = 0.f; dp[x] = 0.f; }
+        }
+        sv = mfma32(__builtin_bit_cast(bf16x8, fr[set + 0]), qf[2 * b], sv);
+        dp = mfma32(__builtin_bit_cast(bf16x8, fr[set + 1]), dof[2 * b], dp);
+        sv = mfma32(__builtin_bit_cast(bf16x8, fr[set + 2]), qf[2 * b + 1], sv);
+        dp = mfma32(__builtin_bit_cast(bf16x8, fr[set + 3]), dof[2 * b + 1], dp);
+        __builtin_amdgcn_sched_barrier(0);
+        if (b == 3) {  // dS^T = P^T o (dP^T - Delta) of this 32-key block, rounded to bf16
 #pragma unroll
-    for (int x = 0; x < 16; ++x) { sv[x] = 0.f; dp[x] = 0.f; }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      sv = mfma32(as_bf16x8(fa[k]), qf[k], sv);
-      dp = mfma32(as_bf16x8(fb[k]), dof[k], dp);
+          for (int x = 0; x < 16; ++x) {
+            float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], c, -lse2));
+            if (general && 32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) pr = 0.f;
+            sv[x] = pr * (dp[x] - dlt);
+          }
+          dsf[0] = as_bf16x8(pack8(sv, 0));
+          dsf[1] = as_bf16x8(pack8(sv, 8));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        const int db = 2 * (b - 4);
+        dq[db] = mfma32(__builtin_bit_cast(bf16x8, fr[set + 0]), dsf[0], dq[db]);
+        dq[db + 1] = mfma32(__builtin_bit_cast(bf16x8, fr[set + 1]), dsf[0], dq[db + 1]);
+        dq[db] = mfma32(__builtin_bit_cast(bf16x8, fr[set + 2]), dsf[1], dq[db]);
+        dq[db + 1] = mfma32(__builtin_bit_cast(bf16x8, fr[set + 3]), dsf[1], dq[db + 1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[4 + k] + kb2 * 8192);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[4 + k] + kb2 * 8192);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      sv = mfma32(as_bf16x8(fa[k]), qf[4 + k], sv);
-      dp = mfma32(as_bf16x8(fb[k]), dof[4 + k], dp);
-    }
-#pragma unroll
-    for (int x = 0; x < 16; ++x) {
-      float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], c, -lse2));
-      if (diag && 32 * kb2 + 8 * (x >> 2) + (x & 3) > rel) pr = 0.f;
-      sv[x] = pr * (dp[x] - dlt);
-    }
-    dsf[2 * kb2 + 0] = as_bf16x8(pack8(sv, 0));
-    dsf[2 * kb2 + 1] = as_bf16x8(pack8(sv, 8));
   };
 
   if (T2 > 0) {
-    load_stage(0);
-    store_stage(smem);
+    load_stage(ht_off(0));
+    store_stage(0);
   }
   __syncthreads();
 
-  for (int32_t t = 0; t < T2; ++t) {
+  // pool offset of the page of half tile t + 1: a new page enters at odd t
+  int64_t off_page = T2 > 0 ? ht_off(0) : 0;
+  const int64_t half_off = (int64_t)64 * p.pool_tok_stride * 2;
+  // st = t mod 2 is a compile-time constant: the loops are unrolled by two
+  auto iteration = [&](const int32_t t, const int st, const bool general) __attribute__((always_inline)) {
     pw.advance(p, g, T, t >> 1, lane);
-    const unsigned char* sb = smem + (t & 1) * DQ_STAGE;
     const bool more = t + 1 < T2;
-    if (more) load_stage(t + 1);
-    const int64_t kfirst = ht_first(t);
-    if (kfirst <= a_wave_max) {  // wave-uniform: some row of this wave sees the half tile
-      const bool diag = kfirst + 63 > a_wave_min;
-      const int rel = (int)(a_i - kfirst) - 4 * hh;  // key index (without the 4 hh term) must be <= rel
-      block(sb, 0, diag, rel);
-      block(sb, 1, diag, rel);
-      // dQ^T += K^T dS^T
-      uint4 fa[4], fb[4];
-      const unsigned char* kt_tile = sb + 32768;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u]);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 4096);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) dq[0] = mfma32(as_bf16x8(fa[u]), dsf[u], dq[0]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) fa[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 2 * 4096);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) dq[1] = mfma32(as_bf16x8(fb[u]), dsf[u], dq[1]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) fb[u] = *reinterpret_cast<const uint4*>(kt_tile + ta[u] + 3 * 4096);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) dq[2] = mfma32(as_bf16x8(fa[u]), dsf[u], dq[2]);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) dq[3] = mfma32(as_bf16x8(fb[u]), dsf[u], dq[3]);
+    if (more) {
+      if (st == 1) off_page = ht_off(t + 1);
+      load_stage(st == 1 ? off_page : off_page + half_off);
     }
-    if (more) store_stage(smem + ((t + 1) & 1) * DQ_STAGE);
+    if (!general) {
+      half_tile(st, false, 0);
+    } else {
+      const int64_t kfirst = ht_first(t);
+      if (kfirst <= a_wave_max)  // wave-uniform: some row of this wave sees the half tile
+        half_tile(st, true, (int)(a_i - kfirst) - 4 * hh);  // key index (without the 4 hh term) must be <= rel
+    }
+    if (more) store_stage(st ^ 1);
     __syncthreads();
+  };
+  {
+    int32_t t = 0;
+    for (; t + 2 <= T_full; t += 2) {
+      iteration(t, 0, false);
+      iteration(t + 1, 1, false);
+    }
+    for (; t < T2; t += 2) {
+      iteration(t, 0, true);
+      if (t + 1 < T2) iteration(t + 1, 1, true);
+    }
   }
 
   if (r_valid) {
@@ -318,7 +359,9 @@ size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)bwd_dq_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -336,7 +379,10 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
     const int tiles = (int)(((int64_t)p.C * p.G + DQ_ROWS - 1) / DQ_ROWS);
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
     ProfScope prof_("bwd_dq_mfma", st);
-    bwd_dq_kernel<<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
+    if (p.pool_tok_stride == HD)
+      bwd_dq_kernel<true><<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
+    else
+      bwd_dq_kernel<false><<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -244,6 +244,7 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 #pragma unroll
         for (int e = 0; e < 4; ++e) fr[nxt + e] = b < 3 ? frag(ko, vo, v, b + 1, e) : frag(kn, vn, v ^ 1, 0, e);
         __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): the batch fetched one batch ago has arrived
+        __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of this batch's matrix instructions
       }
       if (q == 0) s_out = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 0]), qf[2 * b], s_out);
       if (q == 1) of[b] = mfma32(__builtin_bit_cast(bf16x8, fr[cur + 1]), __builtin_bit_cast(bf16x8, p_in[0]), of[b]);
