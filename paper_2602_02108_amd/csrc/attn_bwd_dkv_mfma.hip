@@ -20,15 +20,21 @@
 // column of a row, from a per-lane (row) value split into two bf16 terms.
 //
 // LDS: two stages of 64 query rows x {Q natural, dO natural, Q transposed, dO
-// transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) = 144 KiB.
+// transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) = 144 KiB.  The
+// natural tiles of both stages sit in the lower 64 KiB and the transposed tiles in
+// the next 64 KiB, so that every operand address is a loop-invariant register plus
+// an immediate; the loops are unrolled by two stages to make the stage a constant.
 #include "mfma_common.h"
 
 namespace oomb {
 
 constexpr int KV_THREADS = 512;
-constexpr int KV_STAGE = 4 * 16384;
-constexpr int KV_XCH = 2 * KV_STAGE;
+constexpr int KV_TR = 65536;                   // first transposed tile
+constexpr int KV_XCH = 131072;                 // P exchange
 constexpr int KV_LDS = KV_XCH + 4 * 2 * 2048;
+// tile offsets: natural Q / dO of stage st, transposed Q / dO of stage st (relative to KV_TR)
+__device__ __forceinline__ constexpr int kv_nat(int st, int which) { return st * 32768 + which * 16384; }
+__device__ __forceinline__ constexpr int kv_tr(int st, int which) { return st * 32768 + which * 16384; }
 
 __device__ __forceinline__ uint4 kv_pack8(const f32x16& v, int base) {
   uint4 w;
@@ -136,57 +142,54 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
 #pragma unroll
     for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) ta[k] = tbase ^ (k << 5);
+    for (int k = 0; k < 4; ++k) ta[k] = (tbase ^ (k << 5)) + KV_TR;
   }
-  unsigned char* const xch = smem + KV_XCH + kbw * 4096;
+  const uint32_t xo = KV_XCH + kbw * 4096 + lane * 16;  // this pair's P exchange, this lane's 16 bytes
 
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const uint32_t ts_bytes = (uint32_t)p.q_tok_stride * 2u;
-  // wave-uniform byte offset of row 0 of block b inside Q / dO
-  auto block_base = [&](int32_t b) -> int64_t {
-    const uint32_t tb = div_g(p, (uint32_t)b), hd = (uint32_t)b - tb * p.G;
-    return ((int64_t)(32 * tb) * p.q_tok_stride + (int64_t)(g * p.G + hd) * p.q_head_stride) * 2;
-  };
-  // natural tiles of stage s straight into LDS: this wave moves rows 8 wave .. 8 wave + 7 of the
-  // stage, i.e. rows 8 (wave & 3) .. + 7 of block 2 s + (wave >> 2)
-  uint32_t nat_off[2];
+  // Staging.  This wave moves rows 8 wave .. 8 wave + 7 of a stage's natural tiles and octet `wave`
+  // (rows 16 u + 4 h2 + {0..3, 8..11}, u = wave / 2, h2 = wave % 2) of its transposed tiles; both lie
+  // in block 2 s + wave / 4 of the row space.  Addresses are a wave-uniform block base plus 32-bit
+  // lane offsets (kept opaque so that the loads use the scalar-base addressing form).
+  uint32_t nat_off[2], tr_off[2];  // transposed: rows 16 (u & 1) + 4 h2 and + 8; + k token strides for k = 0..3
 #pragma unroll
   for (int x = 0; x < 2; ++x) {
     const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
     nat_off[x] = (srow & 31) * ts_bytes + (((lane & 15) ^ (srow & 15)) << 4);
+    tr_off[x] = (uint32_t)(16 * ((wave >> 1) & 1) + 4 * (wave & 1) + 8 * x) * ts_bytes + (uint32_t)lane * 4u;
   }
-  // (register staged: a direct global -> LDS load would make the compiler wait for it before
-  // the next LDS read, exposing the whole memory latency)
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  // row-space block of this wave's staging share, kept as (token block, head in group)
+  int32_t ld_tb, ld_hd;
+  {
+    const uint32_t b = (uint32_t)(2 * s0 + (wave >> 2));
+    ld_tb = (int32_t)div_g(p, b);
+    ld_hd = (int32_t)b - ld_tb * p.G;
+  }
+  const int64_t tb_bytes = (int64_t)64 * p.q_tok_stride, hd_bytes = (int64_t)2 * p.q_head_stride;
+  const int64_t g_bytes = (int64_t)g * p.G * hd_bytes;
   u32x4 qn0, qn1, don0, don1;
-  auto load_natural = [&](int32_t s) {
-    const int64_t bb = block_base(2 * s + (wave >> 2));
+  uint32_t qt[8], dot[8];
+  // fetch the stage whose block is (ld_tb, ld_hd), then step to the next stage (two blocks on)
+  auto load_stage = [&]() __attribute__((always_inline)) {
+    const int64_t bb = (int64_t)ld_tb * tb_bytes + (int64_t)ld_hd * hd_bytes + g_bytes;
     const char* qb = reinterpret_cast<const char*>(p.q) + bb;
     const char* ob = reinterpret_cast<const char*>(p.d_o) + bb;
+    asm volatile("" : "+v"(nat_off[0]), "+v"(nat_off[1]), "+v"(tr_off[0]), "+v"(tr_off[1]));
     qn0 = *reinterpret_cast<const u32x4*>(qb + nat_off[0]);
     don0 = *reinterpret_cast<const u32x4*>(ob + nat_off[0]);
     qn1 = *reinterpret_cast<const u32x4*>(qb + nat_off[1]);
     don1 = *reinterpret_cast<const u32x4*>(ob + nat_off[1]);
-  };
-  auto store_natural = [&](unsigned char* sb) {
-    *reinterpret_cast<u32x4*>(sb + (8 * wave) * 256 + lane * 16) = qn0;
-    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave) * 256 + lane * 16) = don0;
-    *reinterpret_cast<u32x4*>(sb + (8 * wave + 4) * 256 + lane * 16) = qn1;
-    *reinterpret_cast<u32x4*>(sb + 16384 + (8 * wave + 4) * 256 + lane * 16) = don1;
-  };
-  // transposed tiles: this wave owns octet `wave` = rows 16 u + 4 h2 + {0..3, 8..11} of the stage
-  // (block 2 s + (u >> 1), tokens 16 (u & 1) + ...), lane l the dims 2 l, 2 l + 1
-  uint32_t qt[8], dot[8];
-  auto load_transposed = [&](int32_t s) {
-    const int u = wave >> 1, h2 = wave & 1;
-    const int64_t bb = block_base(2 * s + (u >> 1)) + (int64_t)(16 * (u & 1) + 4 * h2) * ts_bytes;
-    const char* qb = reinterpret_cast<const char*>(p.q) + bb;
-    const char* ob = reinterpret_cast<const char*>(p.d_o) + bb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const uint32_t ro = (uint32_t)((e & 3) + 8 * (e >> 2)) * ts_bytes;  // wave-uniform
-      qt[e] = *reinterpret_cast<const uint32_t*>(qb + ro + (uint32_t)lane * 4u);
-      dot[e] = *reinterpret_cast<const uint32_t*>(ob + ro + (uint32_t)lane * 4u);
+      uint32_t oe = tr_off[e >> 2] + (uint32_t)(e & 3) * ts_bytes;
+      asm volatile("" : "+v"(oe));
+      qt[e] = *reinterpret_cast<const uint32_t*>(qb + oe);
+      dot[e] = *reinterpret_cast<const uint32_t*>(ob + oe);
     }
+    ld_hd += 2;
+    if (ld_hd >= p.G) { ld_hd -= p.G; ld_tb += 1; }
+    if (ld_hd >= p.G) { ld_hd -= p.G; ld_tb += 1; }
   };
   auto perm4 = [](const uint32_t* r, uint32_t sel) -> uint4 {
     uint4 w;
@@ -196,111 +199,139 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
     w.w = __builtin_amdgcn_perm(r[7], r[6], sel);
     return w;
   };
-  const int tr_o0 = ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = ((2 * lane + 1) * 8 + (wave ^ (lane & 7))) * 16;
-  auto store_transposed = [&](unsigned char* sb) {
-    *reinterpret_cast<uint4*>(sb + 32768 + tr_o0) = perm4(qt, 0x05040100u);
-    *reinterpret_cast<uint4*>(sb + 32768 + tr_o1) = perm4(qt, 0x07060302u);
-    *reinterpret_cast<uint4*>(sb + 49152 + tr_o0) = perm4(dot, 0x05040100u);
-    *reinterpret_cast<uint4*>(sb + 49152 + tr_o1) = perm4(dot, 0x07060302u);
+  const uint32_t nst_o = (8 * wave) * 256 + lane * 16;
+  const uint32_t tr_o0 = KV_TR + ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = tr_o0 + 128;
+  auto store_stage = [&](const int st) __attribute__((always_inline)) {
+    *reinterpret_cast<u32x4*>(smem + (nst_o + kv_nat(st, 0))) = qn0;
+    *reinterpret_cast<u32x4*>(smem + (nst_o + kv_nat(st, 1))) = don0;
+    *reinterpret_cast<u32x4*>(smem + (nst_o + (kv_nat(st, 0) + 1024))) = qn1;
+    *reinterpret_cast<u32x4*>(smem + (nst_o + (kv_nat(st, 1) + 1024))) = don1;
+    *reinterpret_cast<uint4*>(smem + (tr_o0 + kv_tr(st, 0))) = perm4(qt, 0x05040100u);
+    *reinterpret_cast<uint4*>(smem + (tr_o1 + kv_tr(st, 0))) = perm4(qt, 0x07060302u);
+    *reinterpret_cast<uint4*>(smem + (tr_o0 + kv_tr(st, 1))) = perm4(dot, 0x05040100u);
+    *reinterpret_cast<uint4*>(smem + (tr_o1 + kv_tr(st, 1))) = perm4(dot, 0x07060302u);
   };
 
   // per-row statistic of this lane's row in block b: -LSE/c for role 0, -Delta for role 1
   const float* const stat_rs = (role == 0 ? lse2_rs : delta_rs) + (int64_t)g * rows_pad + lq;
   const float stat_scale = role == 0 ? -1.f / c : -1.f;
 
-  if (role == 0) {  // clear this pair's P exchange (the partner reads it before the first P is written)
+  // The partner's first step multiplies zeros (no previous block yet) with the transposed Q tile of
+  // the second stage buffer and with the P exchange: clear both so that no stale NaN pattern is read.
+  {
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 32) = z;
+    *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 32 + 16) = z;
+    if (role == 0) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(xch + k * 1024 + lane * 16) = make_uint4(0, 0, 0, 0);
+      for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + (xo + k * 1024)) = z;
+    }
   }
   if (nb > 0) {
-    load_natural(s0);
-    load_transposed(s0);
-    store_natural(smem + (s0 & 1) * KV_STAGE);
-    store_transposed(smem + (s0 & 1) * KV_STAGE);
+    load_stage();
+    store_stage(0);
   }
   __syncthreads();
 
-  // One loop iteration = one stage = two blocks, two barriers.  The next stage is fetched
-  // into registers at the top and written to the other LDS buffer at the bottom (the last
-  // iteration re-fetches its own stage; nobody reads that copy).  Role 1 works one block
-  // behind role 0 and finishes with one extra half step.  All code between barriers is
-  // straight-line so that no register array needs copies at control-flow joins.
+  // Fragment batches: two sets of four, one batch fetched while the previous one computes.
+  u32x4 fr[8];
+  // natural rows of block `half` of stage st, tile `which`, k-steps 4 kq .. 4 kq + 3
+  auto fetch_nat = [&](const int st, const int which, const int half, const int kq, const int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      fr[set + k] = *reinterpret_cast<const u32x4*>(smem + (na[4 * kq + k] + (kv_nat(st, which) + half * 8192)));
+  };
+  // transposed rows (dim blocks 0..3) of key group 2 half + u of stage st, tile `which`
+  auto fetch_tr = [&](const int st, const int which, const int half, const int u, const int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      fr[set + k] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * half + u] + (kv_tr(st, which) + k * 4096)));
+  };
+  auto wait4 = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): everything but the newest batch has arrived
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto frag = [&](const int idx) __attribute__((always_inline)) -> bf16x8 { return __builtin_bit_cast(bf16x8, fr[idx]); };
+
+  // One loop iteration = one stage = two blocks, two barriers.  The next stage is fetched into
+  // registers at the top and written to the other LDS buffer at the bottom.  Role 1 works one block
+  // behind role 0 and finishes with one extra half step.  All code between barriers is straight-line.
   const int32_t tok_first = (int32_t)(first - first_q);
+  // blocks below this index contain rows that do not see every key of the page (causal diagonal)
+  const int32_t b_diag_end = tok_first + TP - 1 > 0 ? ((tok_first + TP - 1 + 31) / 32) * p.G : 0;
   if (nb > 0) {
     if (role == 0) {
       // S = Q K^T - LSE / c, P = exp2(c S) (masked), P -> partner, dV^T += dO^T P
-      auto block0 = [&](const int32_t blk, const unsigned char* sb, const int half, const float stat_raw) {
+      auto block0 = [&](const int st, const int half, const int32_t blk, const float stat_raw) __attribute__((always_inline)) {
         f32x16 sc;
-        uint4 fa[4], fb[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + na[k] + half * 8192);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + na[4 + k] + half * 8192);
+        if (half == 0) fetch_nat(st, 0, 0, 0, 0);  // (block 1's first batch was fetched at the end of block 0)
+        fetch_nat(st, 0, half, 1, 4);
         const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
-        __builtin_amdgcn_sched_barrier(0);
+        wait4();
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = 0.f;
         sc = mfma32(bias, ones, sc);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fa[k]), kvf[k], sc);
+        for (int k = 0; k < 4; ++k) sc = mfma32(frag(k), kvf[k], sc);
         __builtin_amdgcn_sched_barrier(0);
-        const unsigned char* dt = sb + 49152;  // dO^T fragments for the dV product of this block
+        fetch_tr(st, 1, half, 0, 0);
+        wait4();
 #pragma unroll
-        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 0] + k * 4096);
+        for (int k = 0; k < 4; ++k) sc = mfma32(frag(4 + k), kvf[4 + k], sc);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) sc = mfma32(as_bf16x8(fb[k]), kvf[4 + k], sc);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(dt + ta[2 * half + 1] + k * 4096);
+        fetch_tr(st, 1, half, 1, 4);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
-        const int32_t tok0 = 32 * (int32_t)div_g(p, (uint32_t)blk);  // first chunk token of the block
-        if (tok0 < tok_first + TP - 1) {                              // diagonal block: rows before the key see nothing
-          const int32_t rel = key_rel - tok0 - 4 * hh;
+        if (blk < b_diag_end) {  // diagonal block: rows before the key see nothing
+          const int32_t rel = key_rel - 32 * (int32_t)div_g(p, (uint32_t)blk) - 4 * hh;
 #pragma unroll
           for (int x = 0; x < 16; ++x)
             if (8 * (x >> 2) + (x & 3) < rel) sc[x] = 0.f;
         }
         const uint4 p0 = kv_pack8(sc, 0), p1 = kv_pack8(sc, 8);
-        unsigned char* xb = xch + (blk & 1) * 2048;
-        *reinterpret_cast<uint4*>(xb + lane * 16) = p0;
-        *reinterpret_cast<uint4*>(xb + 1024 + lane * 16) = p1;
+        *reinterpret_cast<uint4*>(smem + (xo + half * 2048)) = p0;
+        *reinterpret_cast<uint4*>(smem + (xo + (half * 2048 + 1024))) = p1;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fa[db]), as_bf16x8(p0), acc[db]);
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(p0), acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (half == 0) {
+          fetch_nat(st, 0, 1, 0, 0);
+          wait4();
+        }
 #pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fb[db]), as_bf16x8(p1), acc[db]);
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(p1), acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
       };
-      float st_a = stat_rs[(int64_t)64 * s0], st_b;
-      for (int32_t s = s0; s < s1; ++s) {
-        const unsigned char* sb = smem + (s & 1) * KV_STAGE;
-        unsigned char* nsb = smem + ((s + 1) & 1) * KV_STAGE;
-        const int32_t sn = s + 1 < s1 ? s + 1 : s;
-        load_natural(sn);
-        load_transposed(sn);
+      float st_a = stat_rs[(int64_t)64 * s0], st_b = 0.f;
+      auto stage0 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
+        const bool more = s + 1 < s1;
+        if (more) load_stage();
         st_b = stat_rs[(int64_t)64 * s + 32];
-        block0(2 * s, sb, 0, st_a);
+        block0(st, 0, 2 * s, st_a);
         __syncthreads();
-        st_a = stat_rs[(int64_t)64 * sn];
-        block0(2 * s + 1, sb, 1, st_b);
-        store_natural(nsb);
-        store_transposed(nsb);
+        if (more) st_a = stat_rs[(int64_t)64 * (s + 1)];
+        block0(st, 1, 2 * s + 1, st_b);
+        if (more) store_stage(st ^ 1);
         __syncthreads();
+      };
+      for (int32_t s = s0; s < s1; s += 2) {
+        stage0(s, 0);
+        if (s + 1 < s1) stage0(s + 1, 1);
       }
     } else {
       // dS = P o dP of the previous block (vector work first), dK^T += Q^T dS, then
       // dP = dO V^T - Delta of the current block.  The partner wave on this SIMD starts its
       // step with matrix work and does its vector work in the middle, so the two waves keep
-      // both pipes busy.  dprev is consumed, dcur produced.
-      auto prev_part = [&](f32x16& dprev, const unsigned char* qtile, const int ph, const unsigned char* xb) {
-        uint4 fa[4], fb[4];
-        const uint4 p0 = *reinterpret_cast<const uint4*>(xb + lane * 16);
-        const uint4 p1 = *reinterpret_cast<const uint4*>(xb + 1024 + lane * 16);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(qtile + ta[2 * ph + 0] + k * 4096);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(qtile + ta[2 * ph + 1] + k * 4096);
+      // both pipes busy.  dprev is consumed, dcur produced.  The previous block of half 0 is
+      // block 1 of the other stage buffer.  Its first transposed batch is already in fr[0..3].
+      auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur, const float stat_raw) __attribute__((always_inline)) {
+        const int pst = half == 0 ? st ^ 1 : st, ph = half ^ 1;
+        const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + ph * 2048));
+        const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (ph * 2048 + 1024)));
+        fetch_tr(pst, 0, ph, 1, 4);
+        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): P and the first batch have arrived
         __builtin_amdgcn_sched_barrier(0);
         const uint32_t pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
@@ -311,49 +342,66 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
         const uint4 s0v = kv_pack8(dprev, 0), s1v = kv_pack8(dprev, 8);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fa[db]), as_bf16x8(s0v), acc[db]);
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(s0v), acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_nat(st, 1, half, 0, 0);
+        wait4();
 #pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(as_bf16x8(fb[db]), as_bf16x8(s1v), acc[db]);
-      };
-      auto cur_part = [&](f32x16& dcur, const unsigned char* sb, const int half, const float stat_raw) {
-        uint4 fa[4], fb[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fa[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[k] + half * 8192);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) fb[k] = *reinterpret_cast<const uint4*>(sb + 16384 + na[4 + k] + half * 8192);
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(s1v), acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_nat(st, 1, half, 1, 4);
         const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
+        wait4();
 #pragma unroll
         for (int x = 0; x < 16; ++x) dcur[x] = 0.f;
-        __builtin_amdgcn_sched_barrier(0);
         dcur = mfma32(bias, ones, dcur);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) dcur = mfma32(as_bf16x8(fa[k]), kvf[k], dcur);
+        for (int k = 0; k < 4; ++k) dcur = mfma32(frag(k), kvf[k], dcur);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_tr(st, 0, half, 0, 0);  // first transposed batch of the next step (this block becomes its previous one)
+        wait4();
 #pragma unroll
-        for (int k = 0; k < 4; ++k) dcur = mfma32(as_bf16x8(fb[k]), kvf[4 + k], dcur);
+        for (int k = 0; k < 4; ++k) dcur = mfma32(frag(4 + k), kvf[4 + k], dcur);
+        __builtin_amdgcn_sched_barrier(0);
       };
       f32x16 dpa, dpb;  // dP of even / odd blocks
 #pragma unroll
       for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
-      float st_a = stat_rs[(int64_t)64 * s0], st_b;
-      for (int32_t s = s0; s < s1; ++s) {
-        const unsigned char* sb = smem + (s & 1) * KV_STAGE;
-        unsigned char* nsb = smem + ((s + 1) & 1) * KV_STAGE;
-        const int32_t sn = s + 1 < s1 ? s + 1 : s;
-        load_natural(sn);
-        load_transposed(sn);
+      float st_a = stat_rs[(int64_t)64 * s0], st_b = 0.f;
+      fetch_tr(1, 0, 1, 0, 0);  // zeros (cleared above): first batch of the first step
+      auto stage1 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
+        const bool more = s + 1 < s1;
+        if (more) load_stage();
         st_b = stat_rs[(int64_t)64 * s + 32];
-        // previous block 2 s - 1 lives in the other stage buffer (for s == s0: zeros times this stage's tile)
-        prev_part(dpb, (s > s0 ? nsb : sb) + 32768, 1, xch + 2048);
-        cur_part(dpa, sb, 0, st_a);
+        step1(st, 0, dpb, dpa, st_a);
         __syncthreads();
-        st_a = stat_rs[(int64_t)64 * sn];
-        prev_part(dpa, sb + 32768, 0, xch);
-        cur_part(dpb, sb, 1, st_b);
-        store_natural(nsb);
-        store_transposed(nsb);
+        if (more) st_a = stat_rs[(int64_t)64 * (s + 1)];
+        step1(st, 1, dpa, dpb, st_b);
+        if (more) store_stage(st ^ 1);
         __syncthreads();
+      };
+      int32_t s = s0;
+      for (; s < s1; s += 2) {
+        stage1(s, 0);
+        if (s + 1 < s1) stage1(s + 1, 1);
       }
-      prev_part(dpb, smem + ((s1 - 1) & 1) * KV_STAGE + 32768, 1, xch + 2048);
+      // the last block's dS and dK^T contribution: its stage buffer is ((s1 - s0 - 1) & 1)
+      {
+        const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + 2048));
+        const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (2048 + 1024)));
+        const uint32_t pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          dpb[2 * k] *= __uint_as_float(pw[k] << 16);
+          dpb[2 * k + 1] *= __uint_as_float(pw[k] & 0xffff0000u);
+        }
+        const uint4 s0v = kv_pack8(dpb, 0), s1v = kv_pack8(dpb, 8);
+        if (((s1 - s0 - 1) & 1) == 0) fetch_tr(0, 0, 1, 1, 4); else fetch_tr(1, 0, 1, 1, 4);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(s0v), acc[db]);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(s1v), acc[db]);
+      }
     }
   }
 
