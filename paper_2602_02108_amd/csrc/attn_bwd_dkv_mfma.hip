@@ -17,7 +17,8 @@
 // In the (query x key) accumulator layout a lane owns one key column and 16 query
 // rows, so the per-row statistics would differ per register.  They are folded into
 // the matrix product instead: one extra MFMA adds -LSE/c (resp. -Delta) to every
-// column of a row, from a per-lane (row) value split into two bf16 terms.
+// column of a row, from a per-lane (row) value split into two bf16 terms (prepared once,
+// together with the swizzled Q / dO tile images, by a layout kernel).
 //
 // LDS: two stages of 64 query rows x {Q natural, dO natural, Q transposed, dO
 // transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) = 144 KiB.  The
@@ -45,16 +46,6 @@ __device__ __forceinline__ uint4 kv_pack8(const f32x16& v, int base) {
   return w;
 }
 
-// A-operand fragment that adds `bias` (one value per row = per lane & 31) to every
-// column of the row when multiplied with the "ones" B fragment: slots 0 and 1 of the
-// contraction hold bias rounded to bf16 and the rounding residual.
-__device__ __forceinline__ bf16x8 bias_frag(float bias, int hh) {
-  const uint32_t hi = pack2_bf16(bias, 0.f) & 0xffffu;
-  const uint32_t lo = pack2_bf16(bias - __uint_as_float(hi << 16), 0.f) & 0xffffu;
-  uint4 w = make_uint4(hh == 0 ? (hi | (lo << 16)) : 0u, 0u, 0u, 0u);
-  return as_bf16x8(w);
-}
-
 template <typename TG> __device__ __forceinline__ void kv_rmw4(TG* ptr, float a, float b, float c2, float d);
 template <> __device__ __forceinline__ void kv_rmw4<float>(float* ptr, float a, float b, float c2, float d) {
   float4 v = *reinterpret_cast<float4*>(ptr);
@@ -77,10 +68,9 @@ template <> __device__ __forceinline__ void kv_rmw4<bf16_t>(bf16_t* ptr, float a
 // partial != nullptr: the unit's dK^T / dV^T go to partial[unit][2][128 keys][128 dims]
 // (fp32, overwritten) instead of the pool; a second kernel adds the slices to the pool.
 template <typename TG>
-__global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const float* __restrict__ delta_rs,
-                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
-                                                             int32_t max_len, int32_t n_split, int xcd_map,
-                                                             float* __restrict__ partial) {
+__global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const unsigned char* __restrict__ img,
+                                                             int32_t n_stages, int32_t max_len, int32_t n_split,
+                                                             int xcd_map, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -147,74 +137,36 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
   const uint32_t xo = KV_XCH + kbw * 4096 + lane * 16;  // this pair's P exchange, this lane's 16 bytes
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  const uint32_t ts_bytes = (uint32_t)p.q_tok_stride * 2u;
-  // Staging.  This wave moves rows 8 wave .. 8 wave + 7 of a stage's natural tiles and octet `wave`
-  // (rows 16 u + 4 h2 + {0..3, 8..11}, u = wave / 2, h2 = wave % 2) of its transposed tiles; both lie
-  // in block 2 s + wave / 4 of the row space.  Addresses are a wave-uniform block base plus 32-bit
-  // lane offsets (kept opaque so that the loads use the scalar-base addressing form).
-  uint32_t nat_off[2], tr_off[2];  // transposed: rows 16 (u & 1) + 4 h2 and + 8; + k token strides for k = 0..3
+  // Staging.  The query-side tiles of a stage (Q and dO, natural and transposed, already swizzled)
+  // are one contiguous 64 KiB image per (KV head, stage); wave w copies bytes 8192 w .. + 8191 of it,
+  // i.e. one half of tile w / 2, through registers, followed by its bias word of each block.
+  constexpr int IMG_BYTES = 65536, IMG_STRIDE = IMG_BYTES + 512;
+  const unsigned char* img_g = img + (int64_t)g * n_stages * IMG_STRIDE;
+  uint32_t ld_off = 8192 * wave + 16 * lane;                 // lane offset inside an image
+  const uint32_t bias_off = IMG_BYTES + (role * 64 + lq) * 4;  // this role's bias word of block 0 (+128 bytes: block 1)
+  // LDS destination: tiles 0, 1 are the natural Q, dO of the stage, tiles 2, 3 the transposed ones
+  const uint32_t st_o = ((wave >> 1) & 1) * 16384 + (wave >> 2) * KV_TR + (wave & 1) * 8192 + 16 * lane;
+  // The copy of the next stage is split in two halves of four registers: the first is fetched at the
+  // top of a stage and written after its first barrier (from then on nobody reads the other buffer),
+  // the second is fetched there and written before the second barrier.
+  u32x4 sg[4];
+  auto load_stage = [&](const int32_t s, const int part) __attribute__((always_inline)) {
+    const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE;
+    asm volatile("" : "+v"(ld_off));
 #pragma unroll
-  for (int x = 0; x < 2; ++x) {
-    const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
-    nat_off[x] = (srow & 31) * ts_bytes + (((lane & 15) ^ (srow & 15)) << 4);
-    tr_off[x] = (uint32_t)(16 * ((wave >> 1) & 1) + 4 * (wave & 1) + 8 * x) * ts_bytes + (uint32_t)lane * 4u;
-  }
-  // row-space block of this wave's staging share, kept as (token block, head in group)
-  int32_t ld_tb, ld_hd;
-  {
-    const uint32_t b = (uint32_t)(2 * s0 + (wave >> 2));
-    ld_tb = (int32_t)div_g(p, b);
-    ld_hd = (int32_t)b - ld_tb * p.G;
-  }
-  const int64_t tb_bytes = (int64_t)64 * p.q_tok_stride, hd_bytes = (int64_t)2 * p.q_head_stride;
-  const int64_t g_bytes = (int64_t)g * p.G * hd_bytes;
-  u32x4 qn0, qn1, don0, don1;
-  uint32_t qt[8], dot[8];
-  // fetch the stage whose block is (ld_tb, ld_hd), then step to the next stage (two blocks on)
-  auto load_stage = [&]() __attribute__((always_inline)) {
-    const int64_t bb = (int64_t)ld_tb * tb_bytes + (int64_t)ld_hd * hd_bytes + g_bytes;
-    const char* qb = reinterpret_cast<const char*>(p.q) + bb;
-    const char* ob = reinterpret_cast<const char*>(p.d_o) + bb;
-    asm volatile("" : "+v"(nat_off[0]), "+v"(nat_off[1]), "+v"(tr_off[0]), "+v"(tr_off[1]));
-    qn0 = *reinterpret_cast<const u32x4*>(qb + nat_off[0]);
-    don0 = *reinterpret_cast<const u32x4*>(ob + nat_off[0]);
-    qn1 = *reinterpret_cast<const u32x4*>(qb + nat_off[1]);
-    don1 = *reinterpret_cast<const u32x4*>(ob + nat_off[1]);
+    for (int k = 0; k < 4; ++k) sg[k] = *reinterpret_cast<const u32x4*>(base + ld_off + 1024 * (4 * part + k));
+  };
+  auto store_stage = [&](const int st, const int part) __attribute__((always_inline)) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      uint32_t oe = tr_off[e >> 2] + (uint32_t)(e & 3) * ts_bytes;
-      asm volatile("" : "+v"(oe));
-      qt[e] = *reinterpret_cast<const uint32_t*>(qb + oe);
-      dot[e] = *reinterpret_cast<const uint32_t*>(ob + oe);
-    }
-    ld_hd += 2;
-    if (ld_hd >= p.G) { ld_hd -= p.G; ld_tb += 1; }
-    if (ld_hd >= p.G) { ld_hd -= p.G; ld_tb += 1; }
+    for (int k = 0; k < 4; ++k) *reinterpret_cast<u32x4*>(smem + (st_o + (st * 32768 + 1024 * (4 * part + k)))) = sg[k];
   };
-  auto perm4 = [](const uint32_t* r, uint32_t sel) -> uint4 {
-    uint4 w;
-    w.x = __builtin_amdgcn_perm(r[1], r[0], sel);
-    w.y = __builtin_amdgcn_perm(r[3], r[2], sel);
-    w.z = __builtin_amdgcn_perm(r[5], r[4], sel);
-    w.w = __builtin_amdgcn_perm(r[7], r[6], sel);
-    return w;
+  // bias A-operand fragment of this lane's row of block 2 s + half (contraction slots 0, 1 = high, low part)
+  auto load_bias = [&](const int32_t s, const int half) __attribute__((always_inline)) -> uint32_t {
+    return *reinterpret_cast<const uint32_t*>(img_g + (int64_t)s * IMG_STRIDE + bias_off + half * 128);
   };
-  const uint32_t nst_o = (8 * wave) * 256 + lane * 16;
-  const uint32_t tr_o0 = KV_TR + ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = tr_o0 + 128;
-  auto store_stage = [&](const int st) __attribute__((always_inline)) {
-    *reinterpret_cast<u32x4*>(smem + (nst_o + kv_nat(st, 0))) = qn0;
-    *reinterpret_cast<u32x4*>(smem + (nst_o + kv_nat(st, 1))) = don0;
-    *reinterpret_cast<u32x4*>(smem + (nst_o + (kv_nat(st, 0) + 1024))) = qn1;
-    *reinterpret_cast<u32x4*>(smem + (nst_o + (kv_nat(st, 1) + 1024))) = don1;
-    *reinterpret_cast<uint4*>(smem + (tr_o0 + kv_tr(st, 0))) = perm4(qt, 0x05040100u);
-    *reinterpret_cast<uint4*>(smem + (tr_o1 + kv_tr(st, 0))) = perm4(qt, 0x07060302u);
-    *reinterpret_cast<uint4*>(smem + (tr_o0 + kv_tr(st, 1))) = perm4(dot, 0x05040100u);
-    *reinterpret_cast<uint4*>(smem + (tr_o1 + kv_tr(st, 1))) = perm4(dot, 0x07060302u);
+  auto bias_of = [&](const uint32_t w) __attribute__((always_inline)) -> bf16x8 {
+    return as_bf16x8(make_uint4(hh == 0 ? w : 0u, 0u, 0u, 0u));
   };
-
-  // per-row statistic of this lane's row in block b: -LSE/c for role 0, -Delta for role 1
-  const float* const stat_rs = (role == 0 ? lse2_rs : delta_rs) + (int64_t)g * rows_pad + lq;
-  const float stat_scale = role == 0 ? -1.f / c : -1.f;
 
   // The partner's first step multiplies zeros (no previous block yet) with the transposed Q tile of
   // the second stage buffer and with the P exchange: clear both so that no stale NaN pattern is read.
@@ -228,8 +180,10 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
     }
   }
   if (nb > 0) {
-    load_stage();
-    store_stage(0);
+    load_stage(s0, 0);
+    store_stage(0, 0);
+    load_stage(s0, 1);
+    store_stage(0, 1);
   }
   __syncthreads();
 
@@ -262,11 +216,11 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
   if (nb > 0) {
     if (role == 0) {
       // S = Q K^T - LSE / c, P = exp2(c S) (masked), P -> partner, dV^T += dO^T P
-      auto block0 = [&](const int st, const int half, const int32_t blk, const float stat_raw) __attribute__((always_inline)) {
+      auto block0 = [&](const int st, const int half, const int32_t blk, const uint32_t bias_w) __attribute__((always_inline)) {
         f32x16 sc;
         if (half == 0) fetch_nat(st, 0, 0, 0, 0);  // (block 1's first batch was fetched at the end of block 0)
         fetch_nat(st, 0, half, 1, 4);
-        const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
+        const bf16x8 bias = bias_of(bias_w);
         wait4();
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = 0.f;
@@ -304,16 +258,20 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
         for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(p1), acc[db]);
         __builtin_amdgcn_sched_barrier(0);
       };
-      float st_a = stat_rs[(int64_t)64 * s0], st_b = 0.f;
+      uint32_t st_a = load_bias(s0, 0), st_b = 0u;
       auto stage0 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) load_stage();
-        st_b = stat_rs[(int64_t)64 * s + 32];
+        if (more) load_stage(s + 1, 0);
+        st_b = load_bias(s, 1);
         block0(st, 0, 2 * s, st_a);
         __syncthreads();
-        if (more) st_a = stat_rs[(int64_t)64 * (s + 1)];
+        if (more) {
+          store_stage(st ^ 1, 0);
+          load_stage(s + 1, 1);
+          st_a = load_bias(s + 1, 0);
+        }
         block0(st, 1, 2 * s + 1, st_b);
-        if (more) store_stage(st ^ 1);
+        if (more) store_stage(st ^ 1, 1);
         __syncthreads();
       };
       for (int32_t s = s0; s < s1; s += 2) {
@@ -326,7 +284,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
       // step with matrix work and does its vector work in the middle, so the two waves keep
       // both pipes busy.  dprev is consumed, dcur produced.  The previous block of half 0 is
       // block 1 of the other stage buffer.  Its first transposed batch is already in fr[0..3].
-      auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur, const float stat_raw) __attribute__((always_inline)) {
+      auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur, const uint32_t bias_w) __attribute__((always_inline)) {
         const int pst = half == 0 ? st ^ 1 : st, ph = half ^ 1;
         const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + ph * 2048));
         const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (ph * 2048 + 1024)));
@@ -350,7 +308,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
         for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(s1v), acc[db]);
         __builtin_amdgcn_sched_barrier(0);
         fetch_nat(st, 1, half, 1, 4);
-        const bf16x8 bias = bias_frag(stat_raw * stat_scale, hh);
+        const bf16x8 bias = bias_of(bias_w);
         wait4();
 #pragma unroll
         for (int x = 0; x < 16; ++x) dcur[x] = 0.f;
@@ -367,17 +325,21 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const flo
       f32x16 dpa, dpb;  // dP of even / odd blocks
 #pragma unroll
       for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
-      float st_a = stat_rs[(int64_t)64 * s0], st_b = 0.f;
+      uint32_t st_a = load_bias(s0, 0), st_b = 0u;
       fetch_tr(1, 0, 1, 0, 0);  // zeros (cleared above): first batch of the first step
       auto stage1 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) load_stage();
-        st_b = stat_rs[(int64_t)64 * s + 32];
+        if (more) load_stage(s + 1, 0);
+        st_b = load_bias(s, 1);
         step1(st, 0, dpb, dpa, st_a);
         __syncthreads();
-        if (more) st_a = stat_rs[(int64_t)64 * (s + 1)];
+        if (more) {
+          store_stage(st ^ 1, 0);
+          load_stage(s + 1, 1);
+          st_a = load_bias(s + 1, 0);
+        }
         step1(st, 1, dpa, dpb, st_b);
-        if (more) store_stage(st ^ 1);
+        if (more) store_stage(st ^ 1, 1);
         __syncthreads();
       };
       int32_t s = s0;
@@ -466,8 +428,8 @@ int32_t dkv_splits(const Params& p, int32_t max_len) {
   return (int32_t)(want < 1 ? 1 : (want > 4 ? 4 : want));
 }
 
-hipError_t launch_bwd_dkv_mfma(const Params& p, const float* delta_rs, const float* lse2_rs, int64_t rows_pad,
-                               int32_t max_len, float* partial_ws, hipStream_t st) {
+hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
+                               float* partial_ws, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)bwd_dkv_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS);
@@ -485,11 +447,11 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const float* delta_rs, const flo
   {
     ProfScope prof_("bwd_dkv_mfma", st);
     if (p.grad_is_bf16)
-      bwd_dkv_kernel<bf16_t><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, max_len,
-                                                                              n_split, xcd_map, partial);
+      bwd_dkv_kernel<bf16_t><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, img, n_stages, max_len, n_split, xcd_map,
+                                                                              partial);
     else
-      bwd_dkv_kernel<float><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, max_len,
-                                                                             n_split, xcd_map, partial);
+      bwd_dkv_kernel<float><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, img, n_stages, max_len, n_split, xcd_map,
+                                                                             partial);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -343,17 +343,78 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Row-space images of Q and dO for the dK/dV kernel.  Every (KV head, page) workgroup
+// of that kernel streams the same query rows; the LDS tiles it needs -- natural and
+// transposed, swizzled -- are laid out once here so that its staging is a plain copy.
+// Image of stage s (row-space blocks 2 s and 2 s + 1, 64 rows) of KV head g, 64 KiB:
+//   [0, 16K)   Q  natural:    row r, granule c (dims 8c..8c+7) at (r * 16 + (c ^ (r & 15))) * 16
+//   [16K, 32K) dO natural
+//   [32K, 48K) Q  transposed: row = dim d, granule o = 2u + hh holds rows 16u + 4hh + {0..3, 8..11};
+//                             at (d * 8 + (o ^ ((d >> 1) & 7))) * 16
+//   [48K, 64K) dO transposed
+// followed by one 256-byte record of bias words per stage: word [which][row], the per-row
+// statistic (-LSE / c for which = 0, -Delta for which = 1) split into bf16 high and low
+// parts, ready to be used as the first two contraction slots of an MFMA A operand.
+constexpr int IMG_BYTES = 65536;
+constexpr int IMG_STRIDE = IMG_BYTES + 512;
+
+__global__ __launch_bounds__(256) void bwd_layout_kernel(Params p, const float* __restrict__ delta_rs,
+                                                         const float* __restrict__ lse2_rs, int64_t rows_pad,
+                                                         unsigned char* __restrict__ img, int32_t n_stages) {
+  __shared__ __align__(16) unsigned char tile[64 * 256 + 64 * 16];  // 64 rows x 128 bf16, rows padded by 16 bytes
+  const int s = blockIdx.x, which = blockIdx.y, g = blockIdx.z, tid = threadIdx.x;
+  unsigned char* out = img + ((int64_t)g * n_stages + s) * IMG_STRIDE;
+  const bf16_t* src = which == 0 ? (const bf16_t*)p.q : (const bf16_t*)p.d_o;
+  // natural rows -> padded LDS tile and natural image
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const int gi = tid + 256 * x, r = gi >> 4, cg = gi & 15;
+    const uint32_t blk = (uint32_t)(2 * s + (r >> 5)), tb = div_g(p, blk);
+    const int i = (int)(32 * tb + (r & 31)), h = g * p.G + (int)(blk - tb * p.G);
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride + 8 * cg);
+    *reinterpret_cast<uint4*>(tile + r * 272 + cg * 16) = v;
+    *reinterpret_cast<uint4*>(out + which * 16384 + (r * 16 + (cg ^ (r & 15))) * 16) = v;
+  }
+  __syncthreads();
+  // transposed image: granule (d, o)
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const int gi = tid + 256 * x, d = gi >> 3, o = gi & 7, u = o >> 1, h2 = o & 1;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int r0 = 16 * u + 4 * h2 + ((2 * e2) & 3) + 8 * ((2 * e2) >> 2), r1 = r0 + 1;
+      const uint32_t lo = *reinterpret_cast<const unsigned short*>(tile + r0 * 272 + d * 2);
+      const uint32_t hi = *reinterpret_cast<const unsigned short*>(tile + r1 * 272 + d * 2);
+      w[e2] = lo | (hi << 16);
+    }
+    *reinterpret_cast<uint4*>(out + 32768 + which * 16384 + (d * 8 + (o ^ ((d >> 1) & 7))) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  // bias words
+  if (tid < 64) {
+    const float c = p.sm_scale * 1.4426950408889634f;
+    const int64_t ri = (int64_t)g * rows_pad + (int64_t)64 * s + tid;
+    const float v = which == 0 ? -lse2_rs[ri] / c : -delta_rs[ri];
+    const uint32_t hi = pack2_bf16(v, 0.f) & 0xffffu;
+    const uint32_t lo = pack2_bf16(v - __uint_as_float(hi << 16), 0.f) & 0xffffu;
+    reinterpret_cast<uint32_t*>(out + IMG_BYTES)[which * 64 + tid] = hi | (lo << 16);
+  }
+}
+
 size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split);
 int32_t dkv_splits(const Params& p, int32_t max_len);
-hipError_t launch_bwd_dkv_mfma(const Params& p, const float* delta_rs, const float* lse2_rs, int64_t rows_pad,
-                               int32_t max_len, float* partial_ws, hipStream_t st);
+hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
+                               float* partial_ws, hipStream_t st);
 
 static inline size_t stats_bytes(const Params& p) {
   return (2 * (size_t)p.Hkv * (size_t)rows_padded(p) * sizeof(float) + 255) & ~(size_t)255;
 }
+static inline int32_t img_stages(const Params& p) { return (p.C / 32) * p.G / 2; }
+static inline size_t img_bytes(const Params& p) { return (size_t)p.Hkv * (size_t)img_stages(p) * IMG_STRIDE; }
 
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
-  return stats_bytes(p) + dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
+  return stats_bytes(p) + img_bytes(p) + dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
 }
 
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
@@ -384,9 +445,15 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
     else
       bwd_dq_kernel<false><<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
   }
+  unsigned char* img = (unsigned char*)ws + stats_bytes(p);
+  {
+    ProfScope prof_("bwd_layout", st);
+    bwd_layout_kernel<<<dim3((unsigned)img_stages(p), 2, (unsigned)p.Hkv), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad, img,
+                                                                                              img_stages(p));
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_bwd_dkv_mfma(p, delta_rs, lse2_rs, rows_pad, max_list_len, (float*)((char*)ws + stats_bytes(p)), st);
+  return launch_bwd_dkv_mfma(p, img, img_stages(p), max_list_len, (float*)((char*)ws + stats_bytes(p) + img_bytes(p)), st);
 }
 
 }  // namespace oomb
