@@ -21,7 +21,7 @@
 // together with the swizzled Q / dO tile images, by a layout kernel).
 //
 // LDS: two stages of 64 query rows x {Q natural, dO natural, Q transposed, dO
-// transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) = 144 KiB.  The
+// transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) + bias words = 145 KiB.  The
 // natural tiles of both stages sit in the lower 64 KiB and the transposed tiles in
 // the next 64 KiB, so that every operand address is a loop-invariant register plus
 // an immediate; the loops are unrolled by two stages to make the stage a constant.
@@ -32,7 +32,8 @@ namespace oomb {
 constexpr int KV_THREADS = 512;
 constexpr int KV_TR = 65536;                   // first transposed tile
 constexpr int KV_XCH = 131072;                 // P exchange
-constexpr int KV_LDS = KV_XCH + 4 * 2 * 2048;
+constexpr int KV_BIAS = KV_XCH + 4 * 2 * 2048;  // bias words: [stage buffer][role][64 rows]
+constexpr int KV_LDS = KV_BIAS + 2 * 512;
 // tile offsets: natural Q / dO of stage st, transposed Q / dO of stage st (relative to KV_TR)
 __device__ __forceinline__ constexpr int kv_nat(int st, int which) { return st * 32768 + which * 16384; }
 __device__ __forceinline__ constexpr int kv_tr(int st, int which) { return st * 32768 + which * 16384; }
@@ -138,102 +139,175 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   // Staging.  The query-side tiles of a stage (Q and dO, natural and transposed, already swizzled)
-  // are one contiguous 64 KiB image per (KV head, stage); wave w copies bytes 8192 w .. + 8191 of it,
-  // i.e. one half of tile w / 2, through registers, followed by its bias word of each block.
+  // and its bias words are one contiguous image per (KV head, stage).  It is copied with direct
+  // global -> LDS loads (no staging registers, so a whole stage of copies can be in flight): every
+  // wave moves 4 KiB of the natural half and 4 KiB of the transposed half, waves 0 and 1 also the
+  // bias words.  The loads are issued from inline assembly because the compiler would otherwise wait
+  // for them before the next LDS read; this kernel orders them itself: they complete in issue order,
+  // so "at most n outstanding" before a barrier publishes everything older than the newest n.
   constexpr int IMG_BYTES = 65536, IMG_STRIDE = IMG_BYTES + 512;
   const unsigned char* img_g = img + (int64_t)g * n_stages * IMG_STRIDE;
-  uint32_t ld_off = 8192 * wave + 16 * lane;                 // lane offset inside an image
-  const uint32_t bias_off = IMG_BYTES + (role * 64 + lq) * 4;  // this role's bias word of block 0 (+128 bytes: block 1)
-  // LDS destination: tiles 0, 1 are the natural Q, dO of the stage, tiles 2, 3 the transposed ones
-  const uint32_t st_o = ((wave >> 1) & 1) * 16384 + (wave >> 2) * KV_TR + (wave & 1) * 8192 + 16 * lane;
-  // The copy of the next stage is split in two halves of four registers: the first is fetched at the
-  // top of a stage and written after its first barrier (from then on nobody reads the other buffer),
-  // the second is fetched there and written before the second barrier.
-  u32x4 sg[4];
-  auto load_stage = [&](const int32_t s, const int part) __attribute__((always_inline)) {
+  const uint32_t cp_off = 4096 * wave + 16 * lane;  // lane offset inside either half of an image
+  const uint32_t cp_bias = 256 * wave + 4 * lane;   // (waves 0, 1) lane offset inside the bias words
+  // natural half of stage s -> stage buffer st.  Its readers finished before the last barrier.
+  auto copy_natural = [&](const int32_t s, const int st) __attribute__((always_inline)) {
     const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE;
-    asm volatile("" : "+v"(ld_off));
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sg[k] = *reinterpret_cast<const u32x4*>(base + ld_off + 1024 * (4 * part + k));
+    const uint32_t dst = st * 32768 + 4096 * wave;
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
+        :: "s"(dst), "v"(cp_off), "s"(base) : "memory");
+    if (wave < 2) {
+      const unsigned char* bb = base + IMG_BYTES;
+      const uint32_t bdst = KV_BIAS + st * 512 + 256 * wave;
+      asm volatile(
+          "s_mov_b32 m0, %0\n\t"
+          "s_nop 0\n\t"
+          "global_load_lds_dword %1, %2\n\t"
+          :: "s"(bdst), "v"(cp_bias), "s"(bb) : "memory");
+    }
   };
-  auto store_stage = [&](const int st, const int part) __attribute__((always_inline)) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) *reinterpret_cast<u32x4*>(smem + (st_o + (st * 32768 + 1024 * (4 * part + k)))) = sg[k];
+  // transposed half of stage s -> stage buffer st.  Only legal after the first barrier of the stage
+  // that precedes s: until then the previous contents are still read.
+  auto copy_transposed = [&](const int32_t s, const int st) __attribute__((always_inline)) {
+    const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE + 32768;
+    const uint32_t dst = KV_TR + st * 32768 + 4096 * wave;
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
+        :: "s"(dst), "v"(cp_off), "s"(base) : "memory");
   };
-  // bias A-operand fragment of this lane's row of block 2 s + half (contraction slots 0, 1 = high, low part)
-  auto load_bias = [&](const int32_t s, const int half) __attribute__((always_inline)) -> uint32_t {
-    return *reinterpret_cast<const uint32_t*>(img_g + (int64_t)s * IMG_STRIDE + bias_off + half * 128);
+  // this role's bias word of this lane's row of block `half` of stage buffer st
+  const uint32_t bias_o = KV_BIAS + (role * 64 + lq) * 4;
+  auto load_bias = [&](const int st, const int half) __attribute__((always_inline)) -> uint32_t {
+    return *reinterpret_cast<const uint32_t*>(smem + (bias_o + (st * 512 + half * 128)));
   };
   auto bias_of = [&](const uint32_t w) __attribute__((always_inline)) -> bf16x8 {
     return as_bf16x8(make_uint4(hh == 0 ? w : 0u, 0u, 0u, 0u));
   };
+  // barrier between the two steps of a stage: the transposed half of this stage (issued one stage
+  // ago) must have landed; the natural half of the next stage (4 loads, 5 for waves 0 and 1) may
+  // still be in flight.  Barrier at the end of a stage: that natural half must have landed, the
+  // transposed half issued after the first barrier (4 loads) may be in flight.
+  auto mid_barrier = [&](const bool more) __attribute__((always_inline)) {
+    if (!more) __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+    else if (wave < 2) __builtin_amdgcn_s_waitcnt(0x0F75);  // vmcnt(5)
+    else __builtin_amdgcn_s_waitcnt(0x0F74);              // vmcnt(4)
+    __syncthreads();
+  };
+  auto end_barrier = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+    __syncthreads();
+  };
 
-  // The partner's first step multiplies zeros (no previous block yet) with the transposed Q tile of
-  // the second stage buffer and with the P exchange: clear both so that no stale NaN pattern is read.
+  // Both roles multiply the transposed tiles of the previous block one step late; in the very first
+  // step that "previous block" is zeros times the transposed tiles of the second stage buffer.  Clear
+  // those tiles and the P exchange so that no stale NaN pattern is read.
   {
     const uint4 z = make_uint4(0, 0, 0, 0);
-    *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 32) = z;
-    *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 32 + 16) = z;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 64 + 16 * k) = z;
     if (role == 0) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + (xo + k * 1024)) = z;
     }
   }
   if (nb > 0) {
-    load_stage(s0, 0);
-    store_stage(0, 0);
-    load_stage(s0, 1);
-    store_stage(0, 1);
+    copy_natural(s0, 0);
+    copy_transposed(s0, 0);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
 
-  // Fragment batches: two sets of four, one batch fetched while the previous one computes.
-  u32x4 fr[8];
-  // natural rows of block `half` of stage st, tile `which`, k-steps 4 kq .. 4 kq + 3
-  auto fetch_nat = [&](const int st, const int which, const int half, const int kq, const int set) __attribute__((always_inline)) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      fr[set + k] = *reinterpret_cast<const u32x4*>(smem + (na[4 * kq + k] + (kv_nat(st, which) + half * 8192)));
-  };
-  // transposed rows (dim blocks 0..3) of key group 2 half + u of stage st, tile `which`
-  auto fetch_tr = [&](const int st, const int which, const int half, const int u, const int set) __attribute__((always_inline)) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      fr[set + k] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * half + u] + (kv_tr(st, which) + k * 4096)));
-  };
-  auto wait4 = [&]() __attribute__((always_inline)) {
-    __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): everything but the newest batch has arrived
-    __builtin_amdgcn_sched_barrier(0);
+  // The matrix phase of a step, the same for both roles: the accumulator chain of the current block
+  // (S = bias + Q K^T for role 0, dP = bias + dO V^T for role 1: A = natural rows of tile `natw`,
+  // B = this wave's K or V rows) interleaved with the transposed-tile product of the PREVIOUS block
+  // (dV^T += dO^T P resp. dK^T += Q^T dS: A = transposed rows of tile `trw`, B = b0 / b1), so that
+  // neighbouring matrix instructions never depend on each other.  Batch j of four: k-steps 2j, 2j+1 of
+  // the chain, dim blocks 2 (j % 2), + 1 of key group j / 2.  One batch is fetched ahead; one wait per
+  // batch.  The previous block of half 0 is block 1 of the other stage buffer.
+  u32x4 fr[12];
+  auto fetch = [&](const int st, const int half, const int natw, const int trw, const int j, const int set) __attribute__((always_inline)) {
+    const int pst = half == 0 ? st ^ 1 : st, ph = half ^ 1, u = j >> 1, db = 2 * (j & 1);
+    fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j] + (kv_nat(st, natw) + half * 8192)));
+    fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * ph + u] + (kv_tr(pst, trw) + db * 4096)));
+    fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j + 1] + (kv_nat(st, natw) + half * 8192)));
+    fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * ph + u] + (kv_tr(pst, trw) + (db + 1) * 4096)));
   };
   auto frag = [&](const int idx) __attribute__((always_inline)) -> bf16x8 { return __builtin_bit_cast(bf16x8, fr[idx]); };
+  // batches 0 and 1 must already be on their way into fr[0..3] and fr[4..7]; three sets rotate, two
+  // batches are in flight while one computes
+  auto matrix_phase = [&](const int st, const int half, const int natw, const int trw, const uint32_t bias_w, f32x16& chain,
+                          const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
+#pragma unroll
+    for (int x = 0; x < 16; ++x) chain[x] = 0.f;
+    chain = mfma32(bias_of(bias_w), ones, chain);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int set = 4 * (j % 3), db = 2 * (j & 1);
+      if (j < 2) {
+        fetch(st, half, natw, trw, j + 2, 4 * ((j + 2) % 3));
+        __builtin_amdgcn_s_waitcnt(0xC87F);  // lgkmcnt(8): this batch has arrived
+      } else if (j == 2) {
+        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4)
+      } else {
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      const bf16x8 bb = as_bf16x8(j < 2 ? b0 : b1);
+      chain = mfma32(frag(set + 0), kvf[2 * j], chain);
+      acc[db] = mfma32(frag(set + 1), bb, acc[db]);
+      chain = mfma32(frag(set + 2), kvf[2 * j + 1], chain);
+      acc[db + 1] = mfma32(frag(set + 3), bb, acc[db + 1]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // the transposed-tile product of the last block (it has no following step): 8 matrix instructions
+  auto flush_phase = [&](const int trw, const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
+    const bool st1 = ((s1 - s0 - 1) & 1) != 0;  // stage buffer of the last block
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const u32x4 f0 = *reinterpret_cast<const u32x4*>(smem + (ta[2 + u] + (kv_tr(0, trw) + k * 4096)));
+        const u32x4 f1 = *reinterpret_cast<const u32x4*>(smem + (ta[2 + u] + (kv_tr(1, trw) + k * 4096)));
+        fr[k] = st1 ? f1 : f0;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] = mfma32(frag(k), as_bf16x8(u == 0 ? b0 : b1), acc[k]);
+    }
+  };
 
-  // One loop iteration = one stage = two blocks, two barriers.  The next stage is fetched into
-  // registers at the top and written to the other LDS buffer at the bottom.  Role 1 works one block
-  // behind role 0 and finishes with one extra half step.  All code between barriers is straight-line.
+  // One loop iteration = one stage = two blocks, two barriers.  The next stage is copied in two parts
+  // (see above).  Role 0's matrix phase comes first in a step and its vector phase last; role 1 is the
+  // other way round, so the two waves of a SIMD keep both pipes busy.  Role 1 works one block behind
+  // role 0 (it needs the P of the block), and both add the transposed-tile product one step late.
   const int32_t tok_first = (int32_t)(first - first_q);
   // blocks below this index contain rows that do not see every key of the page (causal diagonal)
   const int32_t b_diag_end = tok_first + TP - 1 > 0 ? ((tok_first + TP - 1 + 31) / 32) * p.G : 0;
   if (nb > 0) {
     if (role == 0) {
-      // S = Q K^T - LSE / c, P = exp2(c S) (masked), P -> partner, dV^T += dO^T P
-      auto block0 = [&](const int st, const int half, const int32_t blk, const uint32_t bias_w) __attribute__((always_inline)) {
+      // matrix: S = Q K^T - LSE / c  ||  dV^T += dO^T P(previous block);  vector: P = exp2(c S), masked, -> partner
+      uint4 p0 = make_uint4(0, 0, 0, 0), p1 = p0;
+      auto step0 = [&](const int st, const int half, const int32_t blk, const uint32_t bias_w) __attribute__((always_inline)) {
         f32x16 sc;
-        if (half == 0) fetch_nat(st, 0, 0, 0, 0);  // (block 1's first batch was fetched at the end of block 0)
-        fetch_nat(st, 0, half, 1, 4);
-        const bf16x8 bias = bias_of(bias_w);
-        wait4();
-#pragma unroll
-        for (int x = 0; x < 16; ++x) sc[x] = 0.f;
-        sc = mfma32(bias, ones, sc);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) sc = mfma32(frag(k), kvf[k], sc);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_tr(st, 1, half, 0, 0);
-        wait4();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) sc = mfma32(frag(4 + k), kvf[4 + k], sc);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_tr(st, 1, half, 1, 4);
+        if (half == 0) {  // (half 1: fetched at the end of the previous step)
+          fetch(st, 0, 0, 1, 0, 0);
+          fetch(st, 0, 0, 1, 1, 4);
+        }
+        matrix_phase(st, half, 0, 1, bias_w, sc, p0, p1);
+        if (half == 0) {
+          fetch(st, 1, 0, 1, 0, 0);
+          fetch(st, 1, 0, 1, 1, 4);
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
@@ -243,53 +317,35 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
           for (int x = 0; x < 16; ++x)
             if (8 * (x >> 2) + (x & 3) < rel) sc[x] = 0.f;
         }
-        const uint4 p0 = kv_pack8(sc, 0), p1 = kv_pack8(sc, 8);
+        p0 = kv_pack8(sc, 0);
+        p1 = kv_pack8(sc, 8);
         *reinterpret_cast<uint4*>(smem + (xo + half * 2048)) = p0;
         *reinterpret_cast<uint4*>(smem + (xo + (half * 2048 + 1024))) = p1;
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(p0), acc[db]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (half == 0) {
-          fetch_nat(st, 0, 1, 0, 0);
-          wait4();
-        }
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(p1), acc[db]);
-        __builtin_amdgcn_sched_barrier(0);
       };
-      uint32_t st_a = load_bias(s0, 0), st_b = 0u;
       auto stage0 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) load_stage(s + 1, 0);
-        st_b = load_bias(s, 1);
-        block0(st, 0, 2 * s, st_a);
-        __syncthreads();
-        if (more) {
-          store_stage(st ^ 1, 0);
-          load_stage(s + 1, 1);
-          st_a = load_bias(s + 1, 0);
-        }
-        block0(st, 1, 2 * s + 1, st_b);
-        if (more) store_stage(st ^ 1, 1);
-        __syncthreads();
+        if (more) copy_natural(s + 1, st ^ 1);
+        const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
+        step0(st, 0, 2 * s, st_a);
+        mid_barrier(more);
+        if (more) copy_transposed(s + 1, st ^ 1);
+        step0(st, 1, 2 * s + 1, st_b);
+        end_barrier();
       };
       for (int32_t s = s0; s < s1; s += 2) {
         stage0(s, 0);
         if (s + 1 < s1) stage0(s + 1, 1);
       }
+      flush_phase(1, p0, p1);
     } else {
-      // dS = P o dP of the previous block (vector work first), dK^T += Q^T dS, then
-      // dP = dO V^T - Delta of the current block.  The partner wave on this SIMD starts its
-      // step with matrix work and does its vector work in the middle, so the two waves keep
-      // both pipes busy.  dprev is consumed, dcur produced.  The previous block of half 0 is
-      // block 1 of the other stage buffer.  Its first transposed batch is already in fr[0..3].
+      // vector: dS = P o dP of the previous block;  matrix: dP = dO V^T - Delta  ||  dK^T += Q^T dS(previous block)
       auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur, const uint32_t bias_w) __attribute__((always_inline)) {
-        const int pst = half == 0 ? st ^ 1 : st, ph = half ^ 1;
+        const int ph = half ^ 1;
         const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + ph * 2048));
         const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (ph * 2048 + 1024)));
-        fetch_tr(pst, 0, ph, 1, 4);
-        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): P and the first batch have arrived
+        fetch(st, half, 1, 0, 0, 0);
+        fetch(st, half, 1, 0, 1, 4);
+        __builtin_amdgcn_s_waitcnt(0xC87F);  // lgkmcnt(8): P has arrived
         __builtin_amdgcn_sched_barrier(0);
         const uint32_t pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
@@ -299,55 +355,26 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         }
         const uint4 s0v = kv_pack8(dprev, 0), s1v = kv_pack8(dprev, 8);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(s0v), acc[db]);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_nat(st, 1, half, 0, 0);
-        wait4();
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(s1v), acc[db]);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_nat(st, 1, half, 1, 4);
-        const bf16x8 bias = bias_of(bias_w);
-        wait4();
-#pragma unroll
-        for (int x = 0; x < 16; ++x) dcur[x] = 0.f;
-        dcur = mfma32(bias, ones, dcur);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) dcur = mfma32(frag(k), kvf[k], dcur);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch_tr(st, 0, half, 0, 0);  // first transposed batch of the next step (this block becomes its previous one)
-        wait4();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) dcur = mfma32(frag(4 + k), kvf[4 + k], dcur);
-        __builtin_amdgcn_sched_barrier(0);
+        matrix_phase(st, half, 1, 0, bias_w, dcur, s0v, s1v);
       };
       f32x16 dpa, dpb;  // dP of even / odd blocks
 #pragma unroll
       for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
-      uint32_t st_a = load_bias(s0, 0), st_b = 0u;
-      fetch_tr(1, 0, 1, 0, 0);  // zeros (cleared above): first batch of the first step
       auto stage1 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) load_stage(s + 1, 0);
-        st_b = load_bias(s, 1);
+        if (more) copy_natural(s + 1, st ^ 1);
+        const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
         step1(st, 0, dpb, dpa, st_a);
-        __syncthreads();
-        if (more) {
-          store_stage(st ^ 1, 0);
-          load_stage(s + 1, 1);
-          st_a = load_bias(s + 1, 0);
-        }
+        mid_barrier(more);
+        if (more) copy_transposed(s + 1, st ^ 1);
         step1(st, 1, dpa, dpb, st_b);
-        if (more) store_stage(st ^ 1, 1);
-        __syncthreads();
+        end_barrier();
       };
-      int32_t s = s0;
-      for (; s < s1; s += 2) {
+      for (int32_t s = s0; s < s1; s += 2) {
         stage1(s, 0);
         if (s + 1 < s1) stage1(s + 1, 1);
       }
-      // the last block's dS and dK^T contribution: its stage buffer is ((s1 - s0 - 1) & 1)
+      // the last block's dS and dK^T contribution
       {
         const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + 2048));
         const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (2048 + 1024)));
@@ -358,11 +385,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
           dpb[2 * k + 1] *= __uint_as_float(pw[k] & 0xffff0000u);
         }
         const uint4 s0v = kv_pack8(dpb, 0), s1v = kv_pack8(dpb, 8);
-        if (((s1 - s0 - 1) & 1) == 0) fetch_tr(0, 0, 1, 1, 4); else fetch_tr(1, 0, 1, 1, 4);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(db), as_bf16x8(s0v), acc[db]);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) acc[db] = mfma32(frag(4 + db), as_bf16x8(s1v), acc[db]);
+        flush_phase(0, s0v, s1v);
       }
     }
   }
