@@ -94,7 +94,8 @@ def main():
     top_k = w.top_k
     n_max, d_max = desc_at(grow - 1)
     ws_sc = torch.empty(max(api.workspace_bytes(d_max, top_k or 0, api.OP_SCORE_TOPK), 256), dtype=torch.uint8, device=dev)
-    ws_fw = torch.empty(api.workspace_bytes(d_max, 0, api.OP_ATTN_FWD), dtype=torch.uint8, device=dev)
+    ws_fw = torch.empty(api.workspace_bytes(d_max, top_k if top_k is not None else -1, api.OP_ATTN_FWD), dtype=torch.uint8,
+                        device=dev)
     ws_bw = torch.empty(api.workspace_bytes(d_max, top_k if top_k is not None else -1, api.OP_ATTN_BWD), dtype=torch.uint8,
                         device=dev)
     sel = torch.empty((w.Hkv, (top_k or 0) + w.m), dtype=torch.int32, device=dev)

@@ -73,10 +73,10 @@ typedef struct {
 } oomb_attn_desc;
 
 /* Bytes of device workspace `op` needs for this descriptor.  top_k: for
- * OOMB_OP_SCORE_TOPK the number of pages to retrieve; for OOMB_OP_ATTN_BWD the
- * selection list's row stride minus the m local pages (i.e. the top_k the list was
- * built with), or a negative value for a dense call (sel_pages == NULL); ignored
- * for OOMB_OP_ATTN_FWD.  Returns 0 for an invalid descriptor. */
+ * OOMB_OP_SCORE_TOPK the number of pages to retrieve; for OOMB_OP_ATTN_FWD and
+ * OOMB_OP_ATTN_BWD the selection list's row stride minus the m local pages (i.e.
+ * the top_k the list was built with), or a negative value for a dense call
+ * (sel_pages == NULL).  Returns 0 for an invalid descriptor. */
 size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t op);
 
 /*

@@ -147,8 +147,9 @@ def paged_attn_fwd(desc: AttnDesc, q, k_pool, v_pool, page_table, sel_pages=None
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((desc.n_q_heads, desc.chunk_len), dtype=torch.float32, device=q.device)
-    workspace, nbytes = _workspace(desc, 0, OP_ATTN_FWD, q.device, workspace)
     stride = 0 if sel_pages is None else int(sel_pages.stride(0))
+    list_k = -1 if sel_pages is None else stride - desc.chunk_len // desc.page_size
+    workspace, nbytes = _workspace(desc, list_k, OP_ATTN_FWD, q.device, workspace)
     st = lib().oomb_paged_attn_fwd(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
                                    _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(workspace), nbytes,
                                    _stream(q))

@@ -13,7 +13,8 @@ hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st);
 hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st);
 hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
 bool mfma_supported(const Params& p, bool is_bf16);
-hipError_t launch_fwd_mfma(const Params& p, hipStream_t st);
+hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
+size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
 }  // namespace oomb
@@ -93,8 +94,12 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
     case OOMB_OP_SCORE_TOPK:
       if (top_k < 0) return 0;
       return score_workspace_bytes(p);
-    case OOMB_OP_ATTN_FWD:
-      return 256;
+    case OOMB_OP_ATTN_FWD: {
+      int64_t max_len = p.n;
+      if (top_k >= 0 && (int64_t)top_k + p.m < max_len) max_len = (int64_t)top_k + p.m;
+      const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? fwd_mfma_workspace_bytes(p, (int32_t)max_len) : 0;
+      return mfma > 256 ? mfma : 256;
+    }
     case OOMB_OP_ATTN_BWD: {
       // longest selection list the call may be given: top_k retrieved pages + the m local pages
       int64_t max_len = p.n;
@@ -130,7 +135,6 @@ oomb_status oomb_paged_attn_fwd(const oomb_attn_desc* desc, const void* q, const
                                 const int32_t* sel_pages, const int32_t* sel_count,
                                 int32_t sel_stride, void* o, float* lse, void* workspace,
                                 size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p{};
   oomb_status s = check_desc(desc, &p);
   if (s != OOMB_OK) return s;
@@ -144,8 +148,13 @@ oomb_status oomb_paged_attn_fwd(const oomb_attn_desc* desc, const void* q, const
   p.o = o; p.lse = lse;
   const bool bf = desc->dtype == OOMB_BF16;
   hipError_t e;
-  if (!force_generic() && mfma_supported(p, bf)) e = launch_fwd_mfma(p, (hipStream_t)hip_stream);
-  else e = launch_fwd_generic(p, bf, (hipStream_t)hip_stream);
+  if (!force_generic() && mfma_supported(p, bf)) {
+    if (!workspace || workspace_bytes < fwd_mfma_workspace_bytes(p, max_len) || !aligned16(workspace))
+      return OOMB_ERR_WORKSPACE;
+    e = launch_fwd_mfma(p, max_len, workspace, (hipStream_t)hip_stream);
+  } else {
+    e = launch_fwd_generic(p, bf, (hipStream_t)hip_stream);
+  }
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

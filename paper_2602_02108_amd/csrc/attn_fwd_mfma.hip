@@ -29,7 +29,9 @@ constexpr int HT = 64;                    // keys per half tile
 constexpr int HT_BYTES = HT * HD * 2;     // 16 KiB
 constexpr int FW_LDS = 6 * HT_BYTES;      // K0 K1 K2 V0 V1 V2
 
-__global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tiles_per_head, int xcd_map) {
+__global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tiles_per_head, int xcd_map,
+                                                              const unsigned char* __restrict__ k_img,
+                                                              const unsigned char* __restrict__ vt_img, int32_t img_len) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -108,57 +110,27 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 
   // half tile ht: page j = ht / 2, keys 64 (ht % 2) .. + 63 of it
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * HT; };
-  auto ht_off = [&](int32_t ht) -> int64_t {
-    return (int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
-           (int64_t)(ht & 1) * HT * p.pool_tok_stride;
+  // Staging.  K (natural) and V (transposed) half tiles come from images that already have the byte
+  // order of the LDS tiles, one 16 KiB image per half tile of the page list, so a half tile is copied
+  // with direct global -> LDS loads: no staging registers, no LDS store instructions, and a whole
+  // iteration of flight time.  The loads are issued from inline assembly because the compiler would
+  // otherwise wait for them before the next LDS read; the kernel waits for them itself before the
+  // barrier that publishes the data.  Wave w moves bytes 2048 w .. + 2047 of each image.
+  const unsigned char* const k_img_g = k_img + (size_t)g * img_len * 16384;
+  const unsigned char* const vt_img_g = vt_img + (size_t)g * img_len * 16384;
+  const uint32_t cp_off = 2048 * wave + 16 * lane;
+  auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
+    const uint32_t dst = lds_dst + 2048 * wave;
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        :: "s"(dst), "v"(cp_off), "s"(src) : "memory");
   };
-  // this wave's share of a K half tile: 8 rows = two 4-row chunks, staged through registers
-  // (a direct global -> LDS load makes the compiler wait for it before the next LDS read,
-  // which exposes the whole memory latency every iteration).  Lane l of a chunk lands at
-  // granule position l % 16 of row l / 16, so it fetches the granule the swizzle maps there.
-  u32x4 kr0, kr1;
-  uint32_t knat_off[2];
-#pragma unroll
-  for (int x = 0; x < 2; ++x) {
-    const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
-    knat_off[x] = srow * ((uint32_t)p.pool_tok_stride * 2u) + (((lane & 15) ^ (srow & 15)) << 4);
-  }
-  auto load_k = [&](int32_t ht) {
-    const char* base = reinterpret_cast<const char*>((const bf16_t*)p.k_pool + ht_off(ht));
-    kr0 = *reinterpret_cast<const u32x4*>(base + knat_off[0]);
-    kr1 = *reinterpret_cast<const u32x4*>(base + knat_off[1]);
-  };
-  auto store_k = [&](unsigned char* dst) {
-    *reinterpret_cast<u32x4*>(dst + (8 * wave) * 256 + lane * 16) = kr0;
-    *reinterpret_cast<u32x4*>(dst + (8 * wave + 4) * 256 + lane * 16) = kr1;
-  };
-  // this wave's octet (index = wave) of a V half tile: tokens 16u + 4h2 + {0..3, 8..11}
-  uint32_t vr[8], vro[8];
-  {
-    const int u = wave >> 1, h2 = wave & 1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      vro[e] = (uint32_t)(16 * u + 4 * h2 + (e & 3) + 8 * (e >> 2)) * ((uint32_t)p.pool_tok_stride * 2u) + (uint32_t)lane * 4u;
-  }
-  auto load_v = [&](int32_t ht) {
-    const char* base = reinterpret_cast<const char*>((const bf16_t*)p.v_pool + ht_off(ht));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) vr[e] = *reinterpret_cast<const uint32_t*>(base + vro[e]);
-  };
-  auto store_v = [&](unsigned char* dst) {
-    uint4 lo, hi;
-    lo.x = __builtin_amdgcn_perm(vr[1], vr[0], 0x05040100u);
-    lo.y = __builtin_amdgcn_perm(vr[3], vr[2], 0x05040100u);
-    lo.z = __builtin_amdgcn_perm(vr[5], vr[4], 0x05040100u);
-    lo.w = __builtin_amdgcn_perm(vr[7], vr[6], 0x05040100u);
-    hi.x = __builtin_amdgcn_perm(vr[1], vr[0], 0x07060302u);
-    hi.y = __builtin_amdgcn_perm(vr[3], vr[2], 0x07060302u);
-    hi.z = __builtin_amdgcn_perm(vr[5], vr[4], 0x07060302u);
-    hi.w = __builtin_amdgcn_perm(vr[7], vr[6], 0x07060302u);
-    const int d0 = 2 * lane, d1 = 2 * lane + 1;
-    *reinterpret_cast<uint4*>(dst + (d0 * 8 + (wave ^ ((d0 >> 1) & 7))) * 16) = lo;
-    *reinterpret_cast<uint4*>(dst + (d1 * 8 + (wave ^ ((d1 >> 1) & 7))) * 16) = hi;
-  };
+  auto copy_k = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(k_img_g + (size_t)ht * 16384, KB + buf * HT_BYTES); };
+  auto copy_v = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(vt_img_g + (size_t)ht * 16384, buf * HT_BYTES); };
+  auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
 
   // ---- the software pipeline -------------------------------------------------------
   // A unit is 32 keys (half of a half tile).  One step of the pipeline runs three
@@ -276,19 +248,11 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
     if (T_full > T2) T_full = T2;
   }
 
-  // prologue: K_0, K_1, V_0 into LDS; K_2 and V_1 into the staging registers; S_0, S_1, P_0
-  if (T2 > 0) {
-    load_k(0);
-    load_v(0);
-    store_k(kbuf);
-    store_v(vbuf);
-  }
-  if (T2 > 1) {
-    load_k(1);
-    store_k(kbuf + HT_BYTES);
-    load_v(1);
-  }
-  if (T2 > 2) load_k(2);
+  // prologue: K_0, K_1, K_2, V_0, V_1 into LDS; S_0, S_1, P_0
+  if (T2 > 0) { copy_k(0, 0); copy_v(0, 0); }
+  if (T2 > 1) { copy_k(1, 1); copy_v(1, 1); }
+  if (T2 > 2) copy_k(2, 2);
+  copies_landed();
   __syncthreads();
   if (T2 > 0) {
     qk_plain(sA, 0);
@@ -299,18 +263,11 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 #pragma unroll
     for (int q = 0; q < 4; ++q) fr[q] = frag(HT_BYTES, 0, 0, 0, q);
   }
-  // pool offset of the page that holds half tile t + 3 (K) at the top of step B of iteration t; the page
-  // of half tile t + 2 (V) is the same one for even t and the previous one for odd t
-  auto page_off = [&](int32_t j) -> int64_t {
-    return (int64_t)pw.phys(j) * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
-  };
-  int64_t off_k = page_off(T > 1 ? 1 : 0);
-  const int64_t half_off = (int64_t)HT * p.pool_tok_stride;
-
   // iteration t (r = t mod 3): steps A (units 2t | 2t+1 | 2t+2) and B (2t+1 | 2t+2 | 2t+3); K_{t+1}
-  // (buffer r+1) and V_t (buffer r) are read, K_{t+2} (buffer r+2) and V_{t+1} (buffer r+1) are written
-  // before the barrier between A and B.  Three buffers each: a wave still in step B of the previous
-  // iteration reads K_t and V_{t-1}.  The loops are unrolled by three so that r is a constant.
+  // (buffer r+1) and V_t (buffer r) are read.  After the barrier between A and B the copies of K_{t+3}
+  // (buffer r, whose K_t nobody reads any more) and V_{t+2} (buffer r+2, ex V_{t-1}) are issued; they
+  // have to land before the next such barrier.  Three buffers each: a wave still in step B of the
+  // previous iteration reads K_t and V_{t-1}.  The loops are unrolled by three so that r is a constant.
   auto iteration = [&](const int32_t t, const int r, const bool general) __attribute__((always_inline)) {
     const int kc = ((r + 1) % 3) * HT_BYTES, kw = ((r + 2) % 3) * HT_BYTES;
     const int vc = r * HT_BYTES, vw = ((r + 1) % 3) * HT_BYTES;
@@ -321,23 +278,10 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
       relB = t + 1 < T2 ? rel_of(ht_first(t + 1)) : -1;
     }
     step(0, kc, vc, kc + 8192, vc, sB, pB, pA, sA, relA, general);
-    if (t + 2 < T2) store_k(kbuf + kw);
-    if (t + 1 < T2) store_v(smem + vw);
+    copies_landed();
     __syncthreads();
-    {
-      const int64_t off_v = off_k;
-      if ((t & 1) && t + 3 < T2) off_k = page_off((t + 3) >> 1);
-      if (t + 3 < T2) {
-        const char* base = reinterpret_cast<const char*>((const bf16_t*)p.k_pool + off_k + ((t + 3) & 1) * half_off);
-        kr0 = *reinterpret_cast<const u32x4*>(base + knat_off[0]);
-        kr1 = *reinterpret_cast<const u32x4*>(base + knat_off[1]);
-      }
-      if (t + 2 < T2) {
-        const char* base = reinterpret_cast<const char*>((const bf16_t*)p.v_pool + off_v + ((t + 2) & 1) * half_off);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vr[e] = *reinterpret_cast<const uint32_t*>(base + vro[e]);
-      }
-    }
+    if (t + 3 < T2) copy_k(t + 3, r);
+    if (t + 2 < T2) copy_v(t + 2, (r + 2) % 3);
     step(1, kc + 8192, vc, kw, vw, sA, pA, pB, sB, relB, general);
   };
   {
@@ -377,7 +321,15 @@ bool mfma_supported(const Params& p, bool is_bf16) {
   return is_bf16 && p.D == HD && p.P == TP;
 }
 
-hipError_t launch_fwd_mfma(const Params& p, hipStream_t st) {
+size_t kv_image_bytes(const Params& p, int32_t max_len, int kinds);
+hipError_t launch_kv_layout(const Params& p, int32_t max_len, int kinds, void* img, hipStream_t st);
+constexpr int FW_IMG_KINDS = 1 | 8;  // K natural, V transposed
+
+size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
+  return kv_image_bytes(p, max_list_len, FW_IMG_KINDS);
+}
+
+hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)fwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FW_LDS);
@@ -394,7 +346,11 @@ hipError_t launch_fwd_mfma(const Params& p, hipStream_t st) {
   } else {
     blocks = (unsigned)tiles * p.Hkv;
   }
-  { ProfScope prof_("attn_fwd_mfma", st); fwd_mfma_kernel<<<dim3(blocks), dim3(FW_THREADS), FW_LDS, st>>>(p, tiles, xcd_map); }
+  hipError_t e = launch_kv_layout(p, max_list_len, FW_IMG_KINDS, ws, st);
+  if (e != hipSuccess) return e;
+  const unsigned char* k_img = (const unsigned char*)ws;
+  const unsigned char* vt_img = k_img + kv_image_bytes(p, max_list_len, FW_IMG_KINDS) / 2;
+  { ProfScope prof_("attn_fwd_mfma", st); fwd_mfma_kernel<<<dim3(blocks), dim3(FW_THREADS), FW_LDS, st>>>(p, tiles, xcd_map, k_img, vt_img, 2 * max_list_len); }
   return hipGetLastError();
 }
 
