@@ -96,12 +96,10 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restri
 constexpr int DQ_LDS = 6 * 16384;
 constexpr int DQ_KT = 4 * 16384;  // first transposed tile
 
-// CONTIG: the tokens of a page are contiguous (pool_tok_stride == head dim), which turns the row
-// offsets of the staging loads into immediates.
-template <bool CONTIG>
 __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const float* __restrict__ delta_rs,
                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
-                                                            int tiles_per_head, int xcd_map) {
+                                                            int tiles_per_head, int xcd_map,
+                                                            const unsigned char* __restrict__ kv_img, int32_t img_len) {
   extern __shared__ __align__(16) unsigned char smem[];
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
@@ -174,53 +172,33 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
     for (int k = 0; k < 4; ++k) ta[k] = (tbase ^ (k << 5)) + DQ_KT;
   }
 
-  // staging registers: this wave's 8 rows of the natural K and V half tiles (two 4-row
-  // chunks each, source granule pre-swizzled) and its octet of the transposed K half tile
-  const uint32_t ts_bytes = CONTIG ? (uint32_t)(HD * 2) : (uint32_t)p.pool_tok_stride * 2u;
-  // rows 8 wave + (lane / 16) and + 4 of the natural tiles: the swizzle (row & 15) only differs in
-  // bit 2 between the two, so the second offset is the first with that granule bit flipped
-  uint32_t nat_off[2];
-#pragma unroll
-  for (int x = 0; x < 2; ++x) {
-    const uint32_t srow = 8 * wave + 4 * x + (lane >> 4);
-    nat_off[x] = srow * ts_bytes + (((lane & 15) ^ (srow & 15)) << 4);
-  }
-  u32x4 kn0, kn1, vn0, vn1;
-  uint32_t kt[8];
-  // byte offset of half tile ht (page ht / 2, keys 64 (ht % 2) .. + 63) in the pools
-  auto ht_off = [&](int32_t ht) -> int64_t {
-    return ((int64_t)pw.phys(ht >> 1) * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
-            (int64_t)(ht & 1) * 64 * p.pool_tok_stride) * 2;
+  // Staging.  The K natural, V natural and K transposed half tiles come from images that already have
+  // the byte order of the LDS tiles (one 16 KiB image per kind, KV head and half tile of the page
+  // list), so a stage is copied with direct global -> LDS loads: no staging registers, no LDS store
+  // instructions.  They are issued from inline assembly because the compiler would otherwise wait
+  // for them before the next LDS read; the kernel waits for them itself before the barrier that
+  // publishes the stage.  Wave w moves bytes 2048 w .. + 2047 of each image.
+  const size_t kind_bytes = (size_t)p.Hkv * img_len * 16384;
+  const unsigned char* const kn_img = kv_img + (size_t)g * img_len * 16384;
+  const unsigned char* const vn_img = kn_img + kind_bytes;
+  const unsigned char* const kt_img = vn_img + kind_bytes;
+  const uint32_t cp_off = 2048 * wave + 16 * lane;
+  auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
+    const uint32_t dst = lds_dst + 2048 * wave;
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        :: "s"(dst), "v"(cp_off), "s"(src) : "memory");
   };
+  auto copy_stage = [&](const int32_t ht, const int st) __attribute__((always_inline)) {
+    copy_tile(kn_img + (size_t)ht * 16384, st * 32768);
+    copy_tile(vn_img + (size_t)ht * 16384, st * 32768 + 16384);
+    copy_tile(kt_img + (size_t)ht * 16384, DQ_KT + st * 16384);
+  };
+  auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
-  // The empty asm keeps each 32-bit lane offset opaque, so that the loads use the
-  // (scalar base + 32-bit lane offset) addressing form instead of 64-bit lane addresses.
-  const uint32_t kt_lane = (uint32_t)(16 * (wave >> 1) + 4 * (wave & 1)) * ts_bytes + (uint32_t)lane * 4u;
-  auto load_stage = [&](const int64_t off) __attribute__((always_inline)) {
-    const char* kb = reinterpret_cast<const char*>(p.k_pool) + off;
-    const char* vb = reinterpret_cast<const char*>(p.v_pool) + off;
-    uint32_t o0 = nat_off[0], o1 = nat_off[1], ol = kt_lane;
-    asm volatile("" : "+v"(o0), "+v"(o1), "+v"(ol));
-    kn0 = *reinterpret_cast<const u32x4*>(kb + o0);
-    vn0 = *reinterpret_cast<const u32x4*>(vb + o0);
-    kn1 = *reinterpret_cast<const u32x4*>(kb + o1);
-    vn1 = *reinterpret_cast<const u32x4*>(vb + o1);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const char* kr = kb + (uint32_t)((e & 3) + 8 * (e >> 2)) * ts_bytes;  // uniform; an immediate when CONTIG
-      kt[e] = *reinterpret_cast<const uint32_t*>(kr + ol);
-    }
-  };
-  const int tr_o0 = ((2 * lane) * 8 + (wave ^ (lane & 7))) * 16, tr_o1 = ((2 * lane + 1) * 8 + (wave ^ (lane & 7))) * 16;
-  auto store_stage = [&](const int st) __attribute__((always_inline)) {
-    unsigned char* nb = smem + st * 32768;
-    *reinterpret_cast<u32x4*>(nb + (8 * wave) * 256 + lane * 16) = kn0;
-    *reinterpret_cast<u32x4*>(nb + 16384 + (8 * wave) * 256 + lane * 16) = vn0;
-    *reinterpret_cast<u32x4*>(nb + (8 * wave + 4) * 256 + lane * 16) = kn1;
-    *reinterpret_cast<u32x4*>(nb + 16384 + (8 * wave + 4) * 256 + lane * 16) = vn1;
-    *reinterpret_cast<uint4*>(smem + DQ_KT + st * 16384 + tr_o0) = pack_hi_lo(kt, 0x05040100u);
-    *reinterpret_cast<uint4*>(smem + DQ_KT + st * 16384 + tr_o1) = pack_hi_lo(kt, 0x07060302u);
-  };
 
   // One half tile is 12 batches of four matrix instructions.  Per 32-key block kb2: four batches
   // compute S^T and dP^T (fragments: K rows and V rows of k-steps 2b, 2b+1, used alternately so
@@ -290,23 +268,15 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
     }
   };
 
-  if (T2 > 0) {
-    load_stage(ht_off(0));
-    store_stage(0);
-  }
+  if (T2 > 0) copy_stage(0, 0);
+  copies_landed();
   __syncthreads();
 
-  // pool offset of the page of half tile t + 1: a new page enters at odd t
-  int64_t off_page = T2 > 0 ? ht_off(0) : 0;
-  const int64_t half_off = (int64_t)64 * p.pool_tok_stride * 2;
-  // st = t mod 2 is a compile-time constant: the loops are unrolled by two
+  // st = t mod 2 is a compile-time constant: the loops are unrolled by two.  The copy of the next
+  // half tile goes to the other stage, whose readers finished before the last barrier.
   auto iteration = [&](const int32_t t, const int st, const bool general) __attribute__((always_inline)) {
     pw.advance(p, g, T, t >> 1, lane);
-    const bool more = t + 1 < T2;
-    if (more) {
-      if (st == 1) off_page = ht_off(t + 1);
-      load_stage(st == 1 ? off_page : off_page + half_off);
-    }
+    if (t + 1 < T2) copy_stage(t + 1, st ^ 1);
     if (!general) {
       half_tile(st, false, 0);
     } else {
@@ -314,7 +284,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
       if (kfirst <= a_wave_max)  // wave-uniform: some row of this wave sees the half tile
         half_tile(st, true, (int)(a_i - kfirst) - 4 * hh);  // key index (without the 4 hh term) must be <= rel
     }
-    if (more) store_stage(st ^ 1);
+    copies_landed();
     __syncthreads();
   };
   {
@@ -413,22 +383,27 @@ static inline size_t stats_bytes(const Params& p) {
 static inline int32_t img_stages(const Params& p) { return (p.C / 32) * p.G / 2; }
 static inline size_t img_bytes(const Params& p) { return (size_t)p.Hkv * (size_t)img_stages(p) * IMG_STRIDE; }
 
+size_t kv_image_bytes(const Params& p, int32_t max_len, int kinds);
+hipError_t launch_kv_layout(const Params& p, int32_t max_len, int kinds, void* img, hipStream_t st);
+constexpr int DQ_IMG_KINDS = 1 | 2 | 4;  // K natural, V natural, K transposed
+
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
-  return stats_bytes(p) + img_bytes(p) + dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
+  return stats_bytes(p) + img_bytes(p) + kv_image_bytes(p, max_list_len, DQ_IMG_KINDS) +
+         dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
 }
 
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)bwd_dq_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int64_t rows_pad = rows_padded(p);
   float* delta_rs = (float*)ws;
   float* lse2_rs = delta_rs + (size_t)p.Hkv * rows_pad;
+  unsigned char* img = (unsigned char*)ws + stats_bytes(p);  // row-space images of Q / dO
+  unsigned char* kv_img = img + img_bytes(p);                // images of the selected K / V pages
   {
     const int64_t total = (int64_t)p.Hkv * rows_pad;
     ProfScope prof_("bwd_prep", st);
@@ -439,13 +414,12 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   {
     const int tiles = (int)(((int64_t)p.C * p.G + DQ_ROWS - 1) / DQ_ROWS);
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
+    hipError_t e = launch_kv_layout(p, max_list_len, DQ_IMG_KINDS, kv_img, st);
+    if (e != hipSuccess) return e;
     ProfScope prof_("bwd_dq_mfma", st);
-    if (p.pool_tok_stride == HD)
-      bwd_dq_kernel<true><<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
-    else
-      bwd_dq_kernel<false><<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
+    bwd_dq_kernel<<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map, kv_img,
+                                                                   2 * max_list_len);
   }
-  unsigned char* img = (unsigned char*)ws + stats_bytes(p);
   {
     ProfScope prof_("bwd_layout", st);
     bwd_layout_kernel<<<dim3((unsigned)img_stages(p), 2, (unsigned)p.Hkv), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad, img,
@@ -453,7 +427,8 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_bwd_dkv_mfma(p, img, img_stages(p), max_list_len, (float*)((char*)ws + stats_bytes(p) + img_bytes(p)), st);
+  return launch_bwd_dkv_mfma(p, img, img_stages(p), max_list_len,
+                             (float*)(kv_img + kv_image_bytes(p, max_list_len, DQ_IMG_KINDS)), st);
 }
 
 }  // namespace oomb
