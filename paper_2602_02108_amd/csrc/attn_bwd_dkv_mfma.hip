@@ -299,15 +299,10 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       uint4 p0 = make_uint4(0, 0, 0, 0), p1 = p0;
       auto step0 = [&](const int st, const int half, const int32_t blk, const uint32_t bias_w) __attribute__((always_inline)) {
         f32x16 sc;
-        if (half == 0) {  // (half 1: fetched at the end of the previous step)
-          fetch(st, 0, 0, 1, 0, 0);
-          fetch(st, 0, 0, 1, 1, 4);
-        }
+        // (no fetch ahead of the barrier: the transposed tiles of this stage may still be on their way)
+        fetch(st, half, 0, 1, 0, 0);
+        fetch(st, half, 0, 1, 1, 4);
         matrix_phase(st, half, 0, 1, bias_w, sc, p0, p1);
-        if (half == 0) {
-          fetch(st, 1, 0, 1, 0, 0);
-          fetch(st, 1, 0, 1, 1, 4);
-        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
