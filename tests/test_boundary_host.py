@@ -45,6 +45,11 @@ def test_workspace_sizes():
     # a short sparse list is split over more workgroups and needs room for their partial sums
     assert api.workspace_bytes(d, 64, api.OP_ATTN_BWD) > api.workspace_bytes(d, -1, api.OP_ATTN_BWD)
     assert api.workspace_bytes(d, 0, api.OP_ATTN_FWD) > 0
+    # forward: one K and one V image of 32 KiB per (KV head, list entry); a dense call lists all n pages
+    m, n = 4096 // 128, 65536 // 128
+    assert api.workspace_bytes(d, 64, api.OP_ATTN_FWD) >= 4 * (64 + m) * 2 * 32768
+    assert api.workspace_bytes(d, -1, api.OP_ATTN_FWD) >= 4 * n * 2 * 32768
+    assert api.workspace_bytes(d, 64, api.OP_ATTN_FWD) < api.workspace_bytes(d, -1, api.OP_ATTN_FWD)
     assert api.workspace_bytes(d, 0, 99) == 0
     assert api.workspace_bytes(_good_desc(chunk_len=4000), 0, api.OP_ATTN_FWD) == 0
 
@@ -91,6 +96,11 @@ def test_null_pointers_and_workspace_are_rejected():
                                  None) == api.ERR_INVALID_ARG
     assert l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 8, fake, fake, fake, 256,
                                  None) == api.ERR_INVALID_ARG
+    # forward: workspace missing or too small for the page images
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, None, 0,
+                                 None) == api.ERR_WORKSPACE
+    assert l.oomb_paged_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, 256,
+                                 None) == api.ERR_WORKSPACE
     # backward / scoring: workspace missing or too small
     assert l.oomb_paged_attn_bwd(ctypes.byref(d), fake, fake, fake, fake, None, None, 0, fake, fake, fake, fake,
                                  fake, fake, None, 0, None) == api.ERR_WORKSPACE
