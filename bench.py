@@ -175,6 +175,23 @@ def main():
             if len(f) == 5 and f[0] == name and f[1] == "read_bytes" and f[3] == "write_bytes":
                 roof["traffic"] = int(f[2]) + int(f[4])
     kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof.items()}
+    # measured ceilings of this device (outside the timed region): an MFMA issue loop and a streaming copy
+    cbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    ceil_mfma = api.calibrate(0, cbuf)
+    ceil_copy = api.calibrate(1, cbuf)
+    del cbuf
+    props = torch.cuda.get_device_properties(0)
+    roof["measured_ceiling"] = ceil_mfma if roof["bound"] == "mfma" else ceil_copy
+    roof["frac_of_measured_ceiling"] = roof["achieved"] / roof["measured_ceiling"]
+    # per phase: algorithmic FLOPs over the summed kernel times of the phase
+    def phase_ms(names):
+        return sum(kernels[k]["avg_ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
+    fwd_ms = phase_ms(["kv_layout", "attn_fwd_mfma"]) - 0.5 * phase_ms(["kv_layout"])  # kv_layout runs once per phase
+    bwd_ms = phase_ms(["bwd_prep", "bwd_layout", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + 0.5 * phase_ms(["kv_layout"])
+    sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "topk_select"])
+    phases = {"select_ms": sel_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+              "fwd_tflops": 4.0 * w.D * pairs_avg * w.Hq / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else None,
+              "bwd_tflops": 10.0 * w.D * pairs_avg * w.Hq / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else None}
     if "page_score" in kernels:
         by = sum((desc_at(s)[0] // w.P - w.m) for s in range(args.steps)) / args.steps * w.P * w.D * 2 * w.Hkv
         kernels["page_score"]["GB/s"] = by / (kernels["page_score"]["avg_ms"] * 1e-3) / 1e9
@@ -191,6 +208,11 @@ def main():
         "kv_gbps": kv_bytes / dt / 1e9,
         "frac_mfma_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "kernels": kernels,
+        "phases": phases,
+        "device": {"name": props.name, "compute_units": props.multi_processor_count},
+        "ceilings": {"mfma_bf16_tflops_measured": ceil_mfma, "copy_gbs_measured": ceil_copy,
+                     "mfma_bf16_tflops_peak": MFMA_BF16_PEAK_TFLOPS, "hbm_gbs_peak": HBM_PEAK_GBS,
+                     "value_frac_of_measured_mfma": flops / dt / 1e12 / ceil_mfma},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -159,6 +159,20 @@ void oomb_profile_reset(void);
 int32_t oomb_profile_count(void);
 int32_t oomb_profile_read(int32_t idx, char* name, int32_t name_cap, double* total_ms, int64_t* launches);
 
+/*
+ * Benchmark aid (not part of the paper's method): a measured ceiling of the device,
+ * to set kernel rates against something other than the data-sheet peaks.
+ *   which = 0: every SIMD issues independent 32x32x16 bf16 matrix instructions back
+ *              to back; *result = TFLOP/s.  buf is only a sink (>= 4096 bytes).
+ *   which = 1: a streaming kernel copies the first half of buf (device memory,
+ *              16-byte aligned, `bytes` long) to its second half; *result = GB/s
+ *              counting bytes read + bytes written.
+ * Runs on hip_stream and WAITS for the measurement (one warm-up launch, one timed
+ * launch).  Returns OOMB_ERR_INVALID_ARG for NULL / misaligned / too small buffers
+ * or an unknown `which`, OOMB_ERR_LAUNCH if HIP reports an error.
+ */
+oomb_status oomb_calibrate(int32_t which, void* buf, size_t bytes, double* result, void* hip_stream);
+
 const char* oomb_status_string(int32_t status);
 
 /* major * 10000 + minor * 100 + patch */

@@ -18,7 +18,7 @@ OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD = 0, 1, 2
 
 EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
-           "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read"]
+           "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -70,6 +70,8 @@ def lib():
         l.oomb_profile_read.restype = i32
         l.oomb_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int64)]
+        l.oomb_calibrate.restype = i32
+        l.oomb_calibrate.argtypes = [i32, vp, u64, ctypes.POINTER(ctypes.c_double), vp]
         _lib = l
     return _lib
 
@@ -195,3 +197,12 @@ def profile_read() -> dict:
             raise OombError(st, "oomb_profile_read")
         out[name.value.decode()] = (ms.value, n.value)
     return out
+
+
+def calibrate(which: int, buf) -> float:
+    """oomb_calibrate: measured ceiling of the device (0: bf16 MFMA TFLOP/s, 1: copy GB/s, read + write)."""
+    out = ctypes.c_double()
+    st = lib().oomb_calibrate(int(which), _p(buf), buf.numel() * buf.element_size(), ctypes.byref(out), _stream(buf))
+    if st != OK:
+        raise OombError(st, "oomb_calibrate")
+    return out.value

@@ -114,3 +114,13 @@ def test_null_pointers_and_workspace_are_rejected():
     big = _good_desc(ctx_len=(1 << 21) * 128, num_phys_pages=1 << 21)
     assert l.oomb_page_score_topk(ctypes.byref(big), fake, fake, fake, 4, fake, fake, None, fake, 1 << 40,
                                   None) == api.ERR_UNSUPPORTED
+
+
+def test_calibrate_rejects_bad_arguments_before_launch():
+    l = api.lib()
+    out = ctypes.c_double()
+    fake = ctypes.c_void_p(0x1000)
+    assert l.oomb_calibrate(0, None, 1 << 20, ctypes.byref(out), None) == api.ERR_INVALID_ARG
+    assert l.oomb_calibrate(0, fake, 1 << 20, None, None) == api.ERR_INVALID_ARG
+    assert l.oomb_calibrate(1, ctypes.c_void_p(0x1004), 1 << 20, ctypes.byref(out), None) == api.ERR_INVALID_ARG
+    assert l.oomb_calibrate(1, fake, 16, ctypes.byref(out), None) == api.ERR_INVALID_ARG
