@@ -142,9 +142,8 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   // and its bias words are one contiguous image per (KV head, stage).  It is copied with direct
   // global -> LDS loads (no staging registers, so a whole stage of copies can be in flight): every
   // wave moves 4 KiB of the natural half and 4 KiB of the transposed half, waves 0 and 1 also the
-  // bias words.  The loads are issued from inline assembly because the compiler would otherwise wait
-  // for them before the next LDS read; this kernel orders them itself: they complete in issue order,
-  // so "at most n outstanding" before a barrier publishes everything older than the newest n.
+  // bias words.  This kernel orders the copies itself: they complete in issue order, so "at most n
+  // outstanding" before a barrier publishes everything older than the newest n.
   constexpr int IMG_BYTES = 65536, IMG_STRIDE = IMG_BYTES + 512;
   const unsigned char* img_g = img + (int64_t)g * n_stages * IMG_STRIDE;
   const uint32_t cp_off = 4096 * wave + 16 * lane;  // lane offset inside either half of an image
@@ -152,38 +151,13 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   // natural half of stage s -> stage buffer st.  Its readers finished before the last barrier.
   auto copy_natural = [&](const int32_t s, const int st) __attribute__((always_inline)) {
     const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE;
-    const uint32_t dst = st * 32768 + 4096 * wave;
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
-        :: "s"(dst), "v"(cp_off), "s"(base) : "memory");
-    if (wave < 2) {
-      const unsigned char* bb = base + IMG_BYTES;
-      const uint32_t bdst = KV_BIAS + st * 512 + 256 * wave;
-      asm volatile(
-          "s_mov_b32 m0, %0\n\t"
-          "s_nop 0\n\t"
-          "global_load_lds_dword %1, %2\n\t"
-          :: "s"(bdst), "v"(cp_bias), "s"(bb) : "memory");
-    }
+    copy_kib_to_lds<4>(base, cp_off, st * 32768 + 4096 * wave);
+    if (wave < 2) copy_256b_to_lds(base + IMG_BYTES, cp_bias, KV_BIAS + st * 512 + 256 * wave);
   };
   // transposed half of stage s -> stage buffer st.  Only legal after the first barrier of the stage
   // that precedes s: until then the previous contents are still read.
   auto copy_transposed = [&](const int32_t s, const int st) __attribute__((always_inline)) {
-    const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE + 32768;
-    const uint32_t dst = KV_TR + st * 32768 + 4096 * wave;
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
-        :: "s"(dst), "v"(cp_off), "s"(base) : "memory");
+    copy_kib_to_lds<4>(img_g + (int64_t)s * IMG_STRIDE + 32768, cp_off, KV_TR + st * 32768 + 4096 * wave);
   };
   // this role's bias word of this lane's row of block `half` of stage buffer st
   const uint32_t bias_o = KV_BIAS + (role * 64 + lq) * 4;
@@ -198,13 +172,13 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   // still be in flight.  Barrier at the end of a stage: that natural half must have landed, the
   // transposed half issued after the first barrier (4 loads) may be in flight.
   auto mid_barrier = [&](const bool more) __attribute__((always_inline)) {
-    if (!more) __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
-    else if (wave < 2) __builtin_amdgcn_s_waitcnt(0x0F75);  // vmcnt(5)
-    else __builtin_amdgcn_s_waitcnt(0x0F74);              // vmcnt(4)
+    if (!more) wait_copies<0>();
+    else if (wave < 2) wait_copies<5>();
+    else wait_copies<4>();
     __syncthreads();
   };
   auto end_barrier = [&]() __attribute__((always_inline)) {
-    __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+    wait_copies<4>();
     __syncthreads();
   };
 
@@ -224,7 +198,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
     copy_natural(s0, 0);
     copy_transposed(s0, 0);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  wait_copies<0>();
   __syncthreads();
 
   // The matrix phase of a step, the same for both roles: the accumulator chain of the current block

@@ -2,16 +2,16 @@
 // are accumulated in place into the paged gradient pool; Sec. 4.2: the forward's
 // page list is reused).  Page size 128, head dim 128.
 //
-// Three kernels:
-//   bwd_prep : Delta = <dO, O> and LSE * log2(e), both re-laid out in the KV head's
-//              "row space" r = i * G + (h - g * G) and padded to whole tiles.
-//   bwd_dq   : parallel over 256-row tiles (like the forward); per half page of 64
-//              keys: S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - Delta),
-//              dQ^T += K^T dS^T.  Every lane owns one query row.
-//   bwd_dkv  : one workgroup OWNS one (KV head, selected page): it visits every query
-//              row that sees the page, accumulates dK^T and dV^T in registers and
-//              read-modify-writes the page of the gradient pool once, with plain
-//              loads and stores.  No atomics; results do not depend on scheduling.
+// Kernels:
+//   bwd_prep   : Delta = <dO, O> and LSE * log2(e), both re-laid out in the KV head's
+//                "row space" r = 32 b + token-in-block (block b = tb * G + head in group)
+//                and padded to whole tiles.
+//   bwd_layout : row-space images of Q and dO (natural and transposed, swizzled) and
+//                the bias words of the dK/dV kernel, written once per call.
+//   bwd_dq     : parallel over 256-row tiles (like the forward); per 32-key block:
+//                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - Delta),
+//                dQ^T += K^T dS^T.  Every lane owns one query row.
+//   bwd_dkv    : (attn_bwd_dkv_mfma.hip) one workgroup OWNS one (KV head, selected page).
 #include "mfma_common.h"
 
 namespace oomb {
@@ -21,29 +21,12 @@ constexpr int BW_THREADS = BW_WAVES * 64;
 constexpr int DQ_ROWS = 256;
 constexpr int ROW_PAD = 256;  // row-space statistics are padded to a multiple of this
 
-// swizzled byte offset inside a tile whose rows hold GR granules of 16 bytes
-template <int GR> __device__ __forceinline__ int toff(int r, int c) {
-  return (r * GR + (c ^ (GR == 16 ? (r & 15) : ((r >> 1) & 7)))) * 16;
-}
-template <int GR> __device__ __forceinline__ bf16x8 lds_frag(const unsigned char* tile, int r, int c) {
-  return as_bf16x8(*reinterpret_cast<const uint4*>(tile + toff<GR>(r, c)));
-}
-
 __device__ __forceinline__ uint4 pack8(const f32x16& v, int base) {
   uint4 w;
   w.x = pack2_bf16(v[base + 0], v[base + 1]);
   w.y = pack2_bf16(v[base + 2], v[base + 3]);
   w.z = pack2_bf16(v[base + 4], v[base + 5]);
   w.w = pack2_bf16(v[base + 6], v[base + 7]);
-  return w;
-}
-
-__device__ __forceinline__ uint4 pack_hi_lo(const uint32_t* r, uint32_t sel) {
-  uint4 w;
-  w.x = __builtin_amdgcn_perm(r[1], r[0], sel);
-  w.y = __builtin_amdgcn_perm(r[3], r[2], sel);
-  w.z = __builtin_amdgcn_perm(r[5], r[4], sel);
-  w.w = __builtin_amdgcn_perm(r[7], r[6], sel);
   return w;
 }
 
@@ -175,29 +158,22 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   // Staging.  The K natural, V natural and K transposed half tiles come from images that already have
   // the byte order of the LDS tiles (one 16 KiB image per kind, KV head and half tile of the page
   // list), so a stage is copied with direct global -> LDS loads: no staging registers, no LDS store
-  // instructions.  They are issued from inline assembly because the compiler would otherwise wait
-  // for them before the next LDS read; the kernel waits for them itself before the barrier that
-  // publishes the stage.  Wave w moves bytes 2048 w .. + 2047 of each image.
+  // instructions.  The kernel waits for them itself before the barrier that publishes the stage.
+  // Wave w moves bytes 2048 w .. + 2047 of each image.
   const size_t kind_bytes = (size_t)p.Hkv * img_len * 16384;
   const unsigned char* const kn_img = kv_img + (size_t)g * img_len * 16384;
   const unsigned char* const vn_img = kn_img + kind_bytes;
   const unsigned char* const kt_img = vn_img + kind_bytes;
   const uint32_t cp_off = 2048 * wave + 16 * lane;
   auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
-    const uint32_t dst = lds_dst + 2048 * wave;
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
-        :: "s"(dst), "v"(cp_off), "s"(src) : "memory");
+    copy_kib_to_lds<2>(src, cp_off, lds_dst + 2048 * wave);
   };
   auto copy_stage = [&](const int32_t ht, const int st) __attribute__((always_inline)) {
     copy_tile(kn_img + (size_t)ht * 16384, st * 32768);
     copy_tile(vn_img + (size_t)ht * 16384, st * 32768 + 16384);
     copy_tile(kt_img + (size_t)ht * 16384, DQ_KT + st * 16384);
   };
-  auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
+  auto copies_landed = [&]() __attribute__((always_inline)) { wait_copies<0>(); };
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
 
   // One half tile is 12 batches of four matrix instructions.  Per 32-key block kb2: four batches

@@ -105,32 +105,23 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 #pragma unroll
     for (int j = 0; j < 4; ++j) va[j] = vbase ^ (j << 5);
   }
-  unsigned char* const kbuf = smem + KB;
-  unsigned char* const vbuf = smem;
 
   // half tile ht: page j = ht / 2, keys 64 (ht % 2) .. + 63 of it
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * HT; };
   // Staging.  K (natural) and V (transposed) half tiles come from images that already have the byte
   // order of the LDS tiles, one 16 KiB image per half tile of the page list, so a half tile is copied
   // with direct global -> LDS loads: no staging registers, no LDS store instructions, and a whole
-  // iteration of flight time.  The loads are issued from inline assembly because the compiler would
-  // otherwise wait for them before the next LDS read; the kernel waits for them itself before the
-  // barrier that publishes the data.  Wave w moves bytes 2048 w .. + 2047 of each image.
+  // iteration of flight time.  The kernel waits for them itself before the barrier that publishes the
+  // data.  Wave w moves bytes 2048 w .. + 2047 of each image.
   const unsigned char* const k_img_g = k_img + (size_t)g * img_len * 16384;
   const unsigned char* const vt_img_g = vt_img + (size_t)g * img_len * 16384;
   const uint32_t cp_off = 2048 * wave + 16 * lane;
   auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
-    const uint32_t dst = lds_dst + 2048 * wave;
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2\n\t"
-        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
-        :: "s"(dst), "v"(cp_off), "s"(src) : "memory");
+    copy_kib_to_lds<2>(src, cp_off, lds_dst + 2048 * wave);
   };
   auto copy_k = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(k_img_g + (size_t)ht * 16384, KB + buf * HT_BYTES); };
   auto copy_v = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(vt_img_g + (size_t)ht * 16384, buf * HT_BYTES); };
-  auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
+  auto copies_landed = [&]() __attribute__((always_inline)) { wait_copies<0>(); };
 
   // ---- the software pipeline -------------------------------------------------------
   // A unit is 32 keys (half of a half tile).  One step of the pipeline runs three

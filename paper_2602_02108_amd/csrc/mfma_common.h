@@ -1,15 +1,17 @@
 // Building blocks of the bf16 MFMA kernels (gfx950, wave64): vector types, LDS
-// tile layouts and the global -> LDS tile movers.  Page size 128, head dim 128.
+// tile layouts and the direct global -> LDS copy helpers.  Page size 128, head dim 128.
 //
 // MFMA used everywhere: v_mfma_f32_32x32x16_bf16, D(32x32) += A(32x16) * B(16x32).
 //   A operand: lane l holds A[l % 32][8 * (l / 32) + 0..7]
 //   B operand: lane l holds B[8 * (l / 32) + 0..7][l % 32]
 //   C/D:       lane l, register r holds C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32]
 //
-// LDS tiles are 128 rows x 256 bytes (16 granules of 16 bytes).  Granule c of
-// row r is stored at granule position c ^ (r & 15), which makes both the
-// row-per-lane 16-byte operand reads and the row-contiguous writes free of bank
-// conflicts.
+// LDS tiles: natural rows are 256 bytes (16 granules of 16 bytes), granule c of
+// row r stored at granule position c ^ (r & 15); transposed rows are 128 bytes
+// (8 granules), granule o of row d stored at o ^ ((d >> 1) & 7).  Both make the
+// row-per-lane 16-byte operand reads free of bank conflicts.  The tiles are
+// written in this byte order once per call by the layout kernels ("images") and
+// copied into LDS verbatim.
 //   "natural" tile:    row = token, granule c = elements 8c .. 8c+7 of the head dim.
 //   "transposed" tile: row = head-dim index d; granule o = 2 * u + hh holds the
 //                      eight tokens 16u + 4hh + {0,1,2,3, 8,9,10,11}; this is the
@@ -40,97 +42,52 @@ __device__ __forceinline__ f32x16 mfma32(const bf16x8& a, const bf16x8& b, const
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// byte offset of granule c of row r inside a swizzled tile
-__device__ __forceinline__ int tile_off(int r, int c) { return (r * 16 + (c ^ (r & 15))) * 16; }
-
-__device__ __forceinline__ uint4 lds_read16(const unsigned char* tile, int r, int c) {
-  return *reinterpret_cast<const uint4*>(tile + tile_off(r, c));
-}
-
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef __attribute__((address_space(1))) const void* glb_void_ptr;
-
-// s_waitcnt vmcnt(0): every outstanding vector-memory operation of this wave,
-// the direct global -> LDS loads included, has completed.
-__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-// One wave moves 16 rows (four 1 KiB chunks) of a natural tile straight from
-// global memory into LDS (global_load_lds_dwordx4: lane l writes 16 bytes at
-// LDS base + 16 l).  Lane l of a chunk lands at granule position l % 16 of row
-// l / 16, so it fetches the source granule that the swizzle maps there.
-// row0 must be a multiple of 16.  Completion: wait_vmem() + barrier.
-__device__ __forceinline__ void natural_rows_to_lds(const bf16_t* base, int64_t tok_stride, unsigned char* tile,
-                                                    int row0, int lane) {
-  // address = wave-uniform 64-bit base + 32-bit per-lane offset, so that nothing
-  // 64-bit and lane-dependent has to be kept in registers across the main loop
-  const uint32_t ts_bytes = (uint32_t)tok_stride * 2u;
-#pragma unroll
-  for (int x = 0; x < 4; ++x) {
-    const uint32_t lrow = 4 * x + (lane >> 4);
-    const uint32_t c = (lane & 15) ^ (lrow & 15);
-    const char* sbase = reinterpret_cast<const char*>(base + (int64_t)row0 * tok_stride);
-    const char* src = sbase + (lrow * ts_bytes + c * 16u);
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(tile + (row0 + 4 * x) * 256), 16, 0, 0);
+// ---- direct global -> LDS copies ----------------------------------------------------
+// One wave copies `N` consecutive KiB: lane l of chunk k moves the 16 bytes at
+// src + lane_off + 1024 k (lane_off = 16 l plus whatever selects the wave's share) to LDS byte
+// lds_dst + 16 l + 1024 k.  src and lds_dst are wave-uniform.
+//
+// The loads are written in assembly on purpose: given the builtin, the compiler assumes they may
+// alias any LDS read and waits for them (vmcnt(0)) before the next one, which exposes the whole
+// memory latency.  A kernel that uses these copies has to order them itself: they complete in issue
+// order, so "s_waitcnt vmcnt(n)" followed by a barrier publishes every copy but the n newest.  m0
+// holds the LDS address of such a load; it is a reserved register that the compiler only writes
+// next to an instruction that needs it, and the kernels using these helpers contain no other such
+// instruction.
+template <int N>
+__device__ __forceinline__ void copy_kib_to_lds(const unsigned char* src, uint32_t lane_off, uint32_t lds_dst) {
+  static_assert(N == 2 || N == 4, "chunks per call");
+  if (N == 2) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
+  } else {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
+        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
   }
 }
-
-// ---- natural tile: 128 tokens x 128 dims from a (page, head) slab ------------
-// NT threads cooperate; each holds 2048 / NT granules in registers between the
-// global load and the LDS store.
-template <int NT> struct NaturalStage {
-  static constexpr int N = 2048 / NT;
-  uint4 r[N];
-  __device__ __forceinline__ void load(const bf16_t* base, int64_t tok_stride, int tid) {
-#pragma unroll
-    for (int x = 0; x < N; ++x) {
-      const int gi = tid + NT * x;
-      r[x] = *reinterpret_cast<const uint4*>(base + (int64_t)(gi >> 4) * tok_stride + (gi & 15) * 8);
-    }
-  }
-  __device__ __forceinline__ void store(unsigned char* tile, int tid) const {
-#pragma unroll
-    for (int x = 0; x < N; ++x) {
-      const int gi = tid + NT * x;
-      *reinterpret_cast<uint4*>(tile + tile_off(gi >> 4, gi & 15)) = r[x];
-    }
-  }
-};
-
-// ---- transposed tile -----------------------------------------------------------
-// Each wave moves 16 / NW octets; lane l owns head-dim columns 2l, 2l+1 and
-// loads one dword per token (a full 256-byte row per wave instruction).
-template <int NW> struct TransposedStage {
-  static constexpr int OCT = 16 / NW;
-  uint32_t r[OCT][8];
-  __device__ __forceinline__ void load(const bf16_t* base, int64_t tok_stride, int wave, int lane) {
-#pragma unroll
-    for (int x = 0; x < OCT; ++x) {
-      const int o = wave * OCT + x, u = o >> 1, hh = o & 1;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int tok = 16 * u + 4 * hh + (e & 3) + 8 * (e >> 2);
-        r[x][e] = *reinterpret_cast<const uint32_t*>(base + (int64_t)tok * tok_stride + 2 * lane);
-      }
-    }
-  }
-  __device__ __forceinline__ void store(unsigned char* tile, int wave, int lane) const {
-#pragma unroll
-    for (int x = 0; x < OCT; ++x) {
-      const int o = wave * OCT + x;
-      uint4 lo, hi;
-      lo.x = __builtin_amdgcn_perm(r[x][1], r[x][0], 0x05040100u);
-      lo.y = __builtin_amdgcn_perm(r[x][3], r[x][2], 0x05040100u);
-      lo.z = __builtin_amdgcn_perm(r[x][5], r[x][4], 0x05040100u);
-      lo.w = __builtin_amdgcn_perm(r[x][7], r[x][6], 0x05040100u);
-      hi.x = __builtin_amdgcn_perm(r[x][1], r[x][0], 0x07060302u);
-      hi.y = __builtin_amdgcn_perm(r[x][3], r[x][2], 0x07060302u);
-      hi.z = __builtin_amdgcn_perm(r[x][5], r[x][4], 0x07060302u);
-      hi.w = __builtin_amdgcn_perm(r[x][7], r[x][6], 0x07060302u);
-      *reinterpret_cast<uint4*>(tile + tile_off(2 * lane, o)) = lo;
-      *reinterpret_cast<uint4*>(tile + tile_off(2 * lane + 1, o)) = hi;
-    }
-  }
-};
+// one dword per lane (256 bytes per wave)
+__device__ __forceinline__ void copy_256b_to_lds(const unsigned char* src, uint32_t lane_off, uint32_t lds_dst) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %1, %2\n\t"
+      :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
+}
+// at most n of this wave's copies (and other vector-memory operations) are still outstanding
+template <int N> __device__ __forceinline__ void wait_copies() {
+  static_assert(N >= 0 && N < 16, "vmcnt");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
 
 // Page list entries held in registers, 64 per window, two windows deep: lane j of a
 // window holds the logical page id of list entry base + j and its physical page.
