@@ -141,6 +141,56 @@ def page_score_topk(sh: Shape, q, k_pool, page_table, top_k: int):
     return sel, cnt, scores
 
 
+def page_score_topk_cached(sh: Shape, q, kbar_cache, top_k: int):
+    """The selection of page_score_topk with the page means read from kbar_cache [>= n_past][Hkv][D]
+    float32 (logical page order).  Returns (sel, sel_count, scores)."""
+    bf, (q,) = _inputs("f32", q)
+    kb = np.ascontiguousarray(kbar_cache, dtype=np.float32)
+    assert kb.shape[0] >= sh.n_past and kb.shape[1:] == (sh.Hkv, sh.D)
+    sel = np.full((sh.Hkv, top_k + sh.m), -1, dtype=np.int32)
+    cnt = np.zeros(sh.Hkv, dtype=np.int32)
+    scores = np.zeros((sh.Hkv, max(sh.n_past, 0)), dtype=np.float32)
+    d = _desc(sh, bf)
+    _lib("f32").oomb_oracle_page_score_topk_cached(ctypes.byref(d), _ptr(q), _ptr(kb), ctypes.c_int32(top_k),
+                                                   _ptr(sel), _ptr(cnt), _ptr(scores))
+    return sel, cnt, scores
+
+
+def kv_append(sh: Shape, k_chunk, v_chunk, page_table, k_pool, v_pool, kbar_cache=None):
+    """Writes the chunk's K / V [C][Hkv][D] into the m local pages of (copies of) the pools and, if
+    kbar_cache [>= n][Hkv][D] float32 is given, the means of those pages into (a copy of) it.
+    Returns (k_pool, v_pool, kbar_cache)."""
+    bf, (k_chunk, v_chunk, k_pool, v_pool) = _inputs("f32", k_chunk, v_chunk, k_pool, v_pool)
+    k_pool, v_pool = k_pool.copy(), v_pool.copy()
+    pt = _i32(page_table)
+    kb = None if kbar_cache is None else np.ascontiguousarray(kbar_cache, dtype=np.float32).copy()
+    d = _desc(sh, bf)
+    _lib("f32").oomb_oracle_kv_append(ctypes.byref(d), _ptr(k_chunk), _ptr(v_chunk), _ptr(pt), _ptr(k_pool),
+                                      _ptr(v_pool), _ptr(kb) if kb is not None else None)
+    return k_pool, v_pool, kb
+
+
+def page_means(sh: Shape, k_pool, page_table, first: int, count: int, kbar_cache):
+    """Means of logical pages [first, first + count) into (a copy of) kbar_cache [..][Hkv][D] float32."""
+    bf, (k_pool,) = _inputs("f32", k_pool)
+    pt = _i32(page_table)
+    kb = np.ascontiguousarray(kbar_cache, dtype=np.float32).copy()
+    assert kb.shape[0] >= first + count
+    d = _desc(sh, bf)
+    _lib("f32").oomb_oracle_page_means(ctypes.byref(d), _ptr(k_pool), _ptr(pt), ctypes.c_int64(first),
+                                       ctypes.c_int64(count), _ptr(kb))
+    return kb
+
+
+def local_page_list(sh: Shape, window_pages: int):
+    """Page list of a local-attention layer: (sel [Hkv][window_pages + m] int32 padded with -1, sel_count)."""
+    sel = np.full((sh.Hkv, window_pages + sh.m), -1, dtype=np.int32)
+    cnt = np.zeros(sh.Hkv, dtype=np.int32)
+    d = _desc(sh, 0)
+    _lib("f32").oomb_oracle_local_page_list(ctypes.byref(d), ctypes.c_int32(window_pages), _ptr(sel), _ptr(cnt))
+    return sel, cnt
+
+
 def attn_fwd(sh: Shape, q, k_pool, v_pool, page_table, sel=None, sel_count=None, rows=None,
              prec: str = "f32"):
     """O and LSE.  rows: optional int array [n_rows][2] of (h, i) pairs; then O

@@ -137,9 +137,12 @@ static int cand_cmp(const void *a, const void *b) {
   return (x->id > y->id) - (x->id < y->id);
 }
 
-void oomb_oracle_page_score_topk(const oomb_oracle_desc *d, const void *Q, const void *Kpool,
-                                 const int32_t *page_table, int32_t top_k, int32_t *sel,
-                                 int32_t *sel_count, float *scores) {
+/* kbar_cache == NULL: the page means are computed from the keys (S2).  Otherwise they are read from
+ * kbar_cache[l][g][d] (logical page l), as written by oomb_oracle_kv_append / oomb_oracle_page_means,
+ * and Kpool / page_table are not touched. */
+static void score_topk_impl(const oomb_oracle_desc *d, const void *Q, const void *Kpool,
+                            const int32_t *page_table, const float *kbar_cache, int32_t top_k, int32_t *sel,
+                            int32_t *sel_count, float *scores) {
   const int Hq = d->n_q_heads, Hkv = d->n_kv_heads, D = d->head_dim, P = d->page_size;
   const int C = d->chunk_len, G = Hq / Hkv, bf = d->in_is_bf16;
   const int64_t n = d->ctx_len / P;
@@ -175,12 +178,17 @@ void oomb_oracle_page_score_topk(const oomb_oracle_desc *d, const void *Q, const
 
   for (int g = 0; g < Hkv; ++g) {
     for (int64_t l = 0; l < n_past; ++l) {
-      const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
       /* S2 + first step of S3 */
       for (int dd = 0; dd < D; ++dd) {
-        float acc = 0.0f;
-        for (int t = 0; t < P; ++t) acc = acc + (float)ld(Kpool, base + (int64_t)t * D + dd, bf);
-        float kbar = acc * inv_p;
+        float kbar;
+        if (kbar_cache) {
+          kbar = kbar_cache[((size_t)l * Hkv + g) * D + dd];
+        } else {
+          const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
+          float acc = 0.0f;
+          for (int t = 0; t < P; ++t) acc = acc + (float)ld(Kpool, base + (int64_t)t * D + dd, bf);
+          kbar = acc * inv_p;
+        }
         x[dd] = qbar[(size_t)g * D + dd] * kbar;
       }
       /* S3: stride-halving tree */
@@ -208,6 +216,83 @@ void oomb_oracle_page_score_topk(const oomb_oracle_desc *d, const void *Q, const
   free(x);
   free(cand);
   free(keep);
+}
+
+void oomb_oracle_page_score_topk(const oomb_oracle_desc *d, const void *Q, const void *Kpool,
+                                 const int32_t *page_table, int32_t top_k, int32_t *sel,
+                                 int32_t *sel_count, float *scores) {
+  score_topk_impl(d, Q, Kpool, page_table, NULL, top_k, sel, sel_count, scores);
+}
+
+/* The same selection with the page means read from a cache kept by the paged manager (Sec. 4.1:
+ * pages are appended chunk by chunk, so the mean of a page can be taken once, when it is written). */
+void oomb_oracle_page_score_topk_cached(const oomb_oracle_desc *d, const void *Q, const float *kbar_cache,
+                                        int32_t top_k, int32_t *sel, int32_t *sel_count, float *scores) {
+  score_topk_impl(d, Q, NULL, NULL, kbar_cache, top_k, sel, sel_count, scores);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Paged manager, append step (Sec. 4.1): the chunk's keys and values, Kc / Vc [C][Hkv][D] in token
+ * order, become the m = C/P local pages: token i of the chunk goes to
+ * pool[page_table[n_past + i / P]][g][i % P][:], bit for bit.  If kbar_cache is given, the means of
+ * the new pages are written to kbar_cache[n_past + tau][g][:] in the order of step S2 above. */
+void oomb_oracle_kv_append(const oomb_oracle_desc *d, const void *Kc, const void *Vc,
+                           const int32_t *page_table, void *Kpool, void *Vpool, float *kbar_cache) {
+  const int Hkv = d->n_kv_heads, D = d->head_dim, P = d->page_size, C = d->chunk_len, bf = d->in_is_bf16;
+  const int64_t n = d->ctx_len / P, n_past = n - C / P;
+  const size_t esz = bf ? 2 : sizeof(real);
+  for (int i = 0; i < C; ++i)
+    for (int g = 0; g < Hkv; ++g) {
+      const int64_t dst = (((int64_t)page_table[n_past + i / P] * Hkv + g) * P + i % P) * D;
+      const int64_t src = ((int64_t)i * Hkv + g) * D;
+      memcpy((char *)Kpool + (size_t)dst * esz, (const char *)Kc + (size_t)src * esz, (size_t)D * esz);
+      memcpy((char *)Vpool + (size_t)dst * esz, (const char *)Vc + (size_t)src * esz, (size_t)D * esz);
+    }
+  if (!kbar_cache) return;
+  const float inv_p = 1.0f / (float)P;
+  for (int64_t l = n_past; l < n; ++l)
+    for (int g = 0; g < Hkv; ++g) {
+      const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
+      for (int dd = 0; dd < D; ++dd) {
+        float acc = 0.0f;
+        for (int t = 0; t < P; ++t) acc = acc + (float)ld(Kpool, base + (int64_t)t * D + dd, bf);
+        kbar_cache[((size_t)l * Hkv + g) * D + dd] = acc * inv_p;
+      }
+    }
+}
+
+/* Means of logical pages [first, first + count) into kbar_cache (step S2), e.g. to build the cache
+ * for a pool that was filled by other means. */
+void oomb_oracle_page_means(const oomb_oracle_desc *d, const void *Kpool, const int32_t *page_table,
+                            int64_t first, int64_t count, float *kbar_cache) {
+  const int Hkv = d->n_kv_heads, D = d->head_dim, P = d->page_size, bf = d->in_is_bf16;
+  const float inv_p = 1.0f / (float)P;
+  for (int64_t l = first; l < first + count; ++l)
+    for (int g = 0; g < Hkv; ++g) {
+      const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
+      for (int dd = 0; dd < D; ++dd) {
+        float acc = 0.0f;
+        for (int t = 0; t < P; ++t) acc = acc + (float)ld(Kpool, base + (int64_t)t * D + dd, bf);
+        kbar_cache[((size_t)l * Hkv + g) * D + dd] = acc * inv_p;
+      }
+    }
+}
+
+/* Page list of a local-attention layer (Sec. 4.2, natively sparse models: such layers retrieve only
+ * the most recent pages): for every KV head the min(window_pages, n_past) most recent past pages,
+ * then the m local pages, ascending.  sel: [Hkv][window_pages + m]. */
+void oomb_oracle_local_page_list(const oomb_oracle_desc *d, int32_t window_pages, int32_t *sel,
+                                 int32_t *sel_count) {
+  const int Hkv = d->n_kv_heads, P = d->page_size, m = d->chunk_len / P;
+  const int64_t n = d->ctx_len / P, n_past = n - m;
+  const int64_t w = window_pages < n_past ? window_pages : n_past;
+  const int32_t stride = window_pages + m;
+  for (int g = 0; g < Hkv; ++g) {
+    int32_t cnt = 0;
+    for (int64_t l = n_past - w; l < n; ++l) sel[(int64_t)g * stride + cnt++] = (int32_t)l;
+    sel_count[g] = cnt;
+    for (int32_t j = cnt; j < stride; ++j) sel[(int64_t)g * stride + j] = -1;
+  }
 }
 
 /* ------------------------------------------------------------------------- */
