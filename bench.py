@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--workload", default="qwen_sparse_1m")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cached-means", action="store_true",
+                    help="score the pages from cached page means (kept by the paged manager at append time) "
+                         "instead of streaming every past key; the default is the streaming scorer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -104,10 +107,19 @@ def main():
     lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
     dq = torch.empty_like(x["q"])
 
+    kbar_cache = None
+    if args.cached_means and top_k is not None:
+        # the pool is pre-filled; its page means are what the manager would have cached append by append
+        kbar_cache = torch.zeros((n_max // w.P, w.Hkv, w.D), dtype=torch.float32, device=dev)
+        api.page_means(d_max, x["k_pool"], x["page_table"], 0, n_max // w.P, kbar_cache)
+
     def step(s):
         N, desc = desc_at(s)
         if top_k is not None:
-            api.page_score_topk(desc, x["q"], x["k_pool"], x["page_table"], top_k, sel, cnt, workspace=ws_sc)
+            if kbar_cache is not None:
+                api.page_score_topk_cached(desc, x["q"], kbar_cache, top_k, sel, cnt, workspace=ws_sc)
+            else:
+                api.page_score_topk(desc, x["q"], x["k_pool"], x["page_table"], top_k, sel, cnt, workspace=ws_sc)
             sl, ct = sel, cnt
         else:
             sl = ct = None
@@ -188,7 +200,7 @@ def main():
         return sum(kernels[k]["avg_ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
     fwd_ms = phase_ms(["kv_layout", "attn_fwd_mfma"]) - 0.5 * phase_ms(["kv_layout"])  # kv_layout runs once per phase
     bwd_ms = phase_ms(["bwd_prep", "bwd_layout", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + 0.5 * phase_ms(["kv_layout"])
-    sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "topk_select"])
+    sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "page_score_cached", "topk_select"])
     phases = {"select_ms": sel_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
               "fwd_tflops": 4.0 * w.D * pairs_avg * w.Hq / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else None,
               "bwd_tflops": 10.0 * w.D * pairs_avg * w.Hq / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else None}
@@ -204,7 +216,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.D, "page_size": w.P,
                    "chunk": w.C, "history_tokens_first_step": w.N, "history_growth_per_step": w.C,
-                   "top_k_pages": w.top_k, "local_pages": w.m, "grad_pool_dtype": w.grad_dtype},
+                   "top_k_pages": w.top_k, "local_pages": w.m, "grad_pool_dtype": w.grad_dtype,
+                   "scoring": "cached page means" if kbar_cache is not None else "streams every past key"},
         "kv_gbps": kv_bytes / dt / 1e9,
         "frac_mfma_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "kernels": kernels,

@@ -145,6 +145,45 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Paged-manager steps either side of the attention path (Sec. 4.1: the KV cache
+ * grows chunk by chunk in pages).
+ *
+ * oomb_kv_append: the chunk's keys and values become its m = C/P local pages.
+ *   k_chunk, v_chunk [C][Hkv][D] contiguous, device, in   (token order, desc->dtype)
+ *   page_table[n]    device, in: entries n_past .. n-1 name the pages to fill
+ *   k_pool, v_pool   device, in/out: token i of the chunk is copied, bit for bit, to
+ *                    pool[page_table[n_past + i / P]][g][i % P][:]; nothing else is written
+ *   kbar_cache       device, [>= n][Hkv][D] float, may be NULL: rows n_past .. n-1
+ *                    receive the means of the new pages, k_bar = (sum of the P keys,
+ *                    left to right) * (1/P) in binary32 -- the page representative of
+ *                    Sec. 4.2, in the operation order of oomb_page_score_topk.
+ * oomb_page_means: the same means for logical pages first_page .. first_page + n_pages - 1
+ *   (0 <= first_page, first_page + n_pages <= n), e.g. to build the cache of a pool
+ *   that was filled by other means.
+ * oomb_page_score_topk_cached: oomb_page_score_topk with k_bar read from kbar_cache
+ *   (rows 0 .. n_past-1) instead of being recomputed from the keys; same scores, bit
+ *   for bit, same lists; reads n_past * Hkv * D floats instead of every past key.
+ *   Workspace as for OOMB_OP_SCORE_TOPK.
+ * oomb_local_page_list (Sec. 4.2, natively sparse models: local-attention layers
+ *   retrieve only the most recent pages): for every KV head the min(window_pages,
+ *   n_past) most recent past pages followed by the m local pages, ascending.
+ *   sel_pages [Hkv][window_pages + m] (unused tail = -1), sel_count [Hkv].
+ * Errors as for the other entry points (NULL / misaligned pointers, bad ranges:
+ * OOMB_ERR_INVALID_ARG; nothing is launched).
+ */
+oomb_status oomb_kv_append(const oomb_attn_desc* desc, const void* k_chunk, const void* v_chunk,
+                           const int32_t* page_table, void* k_pool, void* v_pool, float* kbar_cache,
+                           void* hip_stream);
+oomb_status oomb_page_means(const oomb_attn_desc* desc, const void* k_pool, const int32_t* page_table,
+                            int64_t first_page, int64_t n_pages, float* kbar_cache, void* hip_stream);
+oomb_status oomb_page_score_topk_cached(const oomb_attn_desc* desc, const void* q, const float* kbar_cache,
+                                        int32_t top_k, int32_t* sel_pages, int32_t* sel_count,
+                                        float* scores_out, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream);
+oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_pages, int32_t* sel_pages,
+                                 int32_t* sel_count, void* hip_stream);
+
+/*
  * Benchmark aid (not part of the paper's method): per-kernel device time.  While
  * enabled, every kernel the library launches is bracketed by two HIP events
  * recorded on the caller's stream (events are host objects created on demand; no

@@ -18,7 +18,8 @@ OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD = 0, 1, 2
 
 EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
-           "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate"]
+           "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
+           "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -70,6 +71,15 @@ def lib():
         l.oomb_profile_read.restype = i32
         l.oomb_profile_read.argtypes = [i32, ctypes.c_char_p, i32, ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int64)]
+        i64, fp = ctypes.c_int64, ctypes.c_void_p
+        l.oomb_kv_append.restype = i32
+        l.oomb_kv_append.argtypes = [dp, vp, vp, vp, vp, vp, fp, vp]
+        l.oomb_page_means.restype = i32
+        l.oomb_page_means.argtypes = [dp, vp, vp, i64, i64, fp, vp]
+        l.oomb_page_score_topk_cached.restype = i32
+        l.oomb_page_score_topk_cached.argtypes = [dp, vp, fp, i32, vp, vp, vp, vp, u64, vp]
+        l.oomb_local_page_list.restype = i32
+        l.oomb_local_page_list.argtypes = [dp, i32, vp, vp, vp]
         l.oomb_calibrate.restype = i32
         l.oomb_calibrate.argtypes = [i32, vp, u64, ctypes.POINTER(ctypes.c_double), vp]
         _lib = l
@@ -206,3 +216,49 @@ def calibrate(which: int, buf) -> float:
     if st != OK:
         raise OombError(st, "oomb_calibrate")
     return out.value
+
+
+def kv_append(desc: AttnDesc, k_chunk, v_chunk, page_table, k_pool, v_pool, kbar_cache=None) -> None:
+    """oomb_kv_append: the chunk's K / V [C][Hkv][D] into its local pages (+ their means into kbar_cache)."""
+    st = lib().oomb_kv_append(ctypes.byref(desc), _p(k_chunk), _p(v_chunk), _p(page_table), _p(k_pool), _p(v_pool),
+                              _p(kbar_cache), _stream(k_pool))
+    if st != OK:
+        raise OombError(st, "oomb_kv_append")
+
+
+def page_means(desc: AttnDesc, k_pool, page_table, first_page: int, n_pages: int, kbar_cache) -> None:
+    """oomb_page_means: means of logical pages [first_page, first_page + n_pages) into kbar_cache."""
+    st = lib().oomb_page_means(ctypes.byref(desc), _p(k_pool), _p(page_table), int(first_page), int(n_pages),
+                               _p(kbar_cache), _stream(k_pool))
+    if st != OK:
+        raise OombError(st, "oomb_page_means")
+
+
+def page_score_topk_cached(desc: AttnDesc, q, kbar_cache, top_k: int, sel_pages=None, sel_count=None,
+                           scores_out=None, workspace=None):
+    """oomb_page_score_topk_cached.  Returns (sel_pages [Hkv][top_k + m] int32, sel_count [Hkv] int32)."""
+    m = desc.chunk_len // desc.page_size
+    if sel_pages is None:
+        sel_pages = torch.empty((desc.n_kv_heads, top_k + m), dtype=torch.int32, device=q.device)
+    if sel_count is None:
+        sel_count = torch.empty((desc.n_kv_heads,), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(desc, top_k, OP_SCORE_TOPK, q.device, workspace)
+    st = lib().oomb_page_score_topk_cached(ctypes.byref(desc), _p(q), _p(kbar_cache), int(top_k), _p(sel_pages),
+                                           _p(sel_count), _p(scores_out), _p(workspace), nbytes, _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_page_score_topk_cached")
+    return sel_pages, sel_count
+
+
+def local_page_list(desc: AttnDesc, window_pages: int, device, sel_pages=None, sel_count=None):
+    """oomb_local_page_list.  Returns (sel_pages [Hkv][window_pages + m] int32, sel_count [Hkv] int32)."""
+    m = desc.chunk_len // desc.page_size
+    if sel_pages is None:
+        sel_pages = torch.empty((desc.n_kv_heads, window_pages + m), dtype=torch.int32, device=device)
+    if sel_count is None:
+        sel_count = torch.empty((desc.n_kv_heads,), dtype=torch.int32, device=device)
+    st = lib().oomb_local_page_list(ctypes.byref(desc), int(window_pages), _p(sel_pages), _p(sel_count),
+                                    _stream(sel_pages))
+    if st != OK:
+        raise OombError(st, "oomb_local_page_list")
+    return sel_pages, sel_count

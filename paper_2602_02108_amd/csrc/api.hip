@@ -7,8 +7,12 @@
 
 namespace oomb {
 size_t score_workspace_bytes(const Params& p);
-hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel,
-                             int32_t* sel_count, float* scores_out, void* ws, hipStream_t st);
+hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel, int32_t* sel_count,
+                             float* scores_out, void* ws, const float* kbar_cache, hipStream_t st);
+hipError_t launch_kv_append(const Params& p, bool is_bf16, const void* kc, const void* vc, void* k_pool, void* v_pool,
+                            float* cache, hipStream_t st);
+hipError_t launch_page_means(const Params& p, bool is_bf16, int64_t first, int64_t count, float* cache, hipStream_t st);
+hipError_t launch_local_page_list(const Params& p, int32_t window, int32_t* sel, int32_t* sel_count, hipStream_t st);
 hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st);
 hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st);
 hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
@@ -126,7 +130,64 @@ oomb_status oomb_page_score_topk(const oomb_attn_desc* desc, const void* q, cons
   if (!workspace || workspace_bytes < score_workspace_bytes(p)) return OOMB_ERR_WORKSPACE;
   p.q = q; p.k_pool = k_pool; p.page_table = page_table;
   hipError_t e = launch_score_topk(p, desc->dtype == OOMB_BF16, top_k, sel_pages, sel_count, scores_out,
-                                   workspace, (hipStream_t)hip_stream);
+                                   workspace, nullptr, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_page_score_topk_cached(const oomb_attn_desc* desc, const void* q, const float* kbar_cache,
+                                        int32_t top_k, int32_t* sel_pages, int32_t* sel_count, float* scores_out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !kbar_cache || !sel_pages || !sel_count || top_k < 0) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(kbar_cache)) return OOMB_ERR_INVALID_ARG;
+  if (p.n_past > (1 << 20)) return OOMB_ERR_UNSUPPORTED;
+  if (!workspace || workspace_bytes < score_workspace_bytes(p)) return OOMB_ERR_WORKSPACE;
+  p.q = q;
+  hipError_t e = launch_score_topk(p, desc->dtype == OOMB_BF16, top_k, sel_pages, sel_count, scores_out,
+                                   workspace, kbar_cache, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_kv_append(const oomb_attn_desc* desc, const void* k_chunk, const void* v_chunk,
+                           const int32_t* page_table, void* k_pool, void* v_pool, float* kbar_cache,
+                           void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!k_chunk || !v_chunk || !page_table || !k_pool || !v_pool) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(k_chunk) || !aligned16(v_chunk) || !aligned16(k_pool) || !aligned16(v_pool) ||
+      (kbar_cache && !aligned16(kbar_cache)))
+    return OOMB_ERR_INVALID_ARG;
+  p.page_table = page_table;
+  p.k_pool = k_pool;
+  hipError_t e = launch_kv_append(p, desc->dtype == OOMB_BF16, k_chunk, v_chunk, k_pool, v_pool, kbar_cache,
+                                  (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_page_means(const oomb_attn_desc* desc, const void* k_pool, const int32_t* page_table,
+                            int64_t first_page, int64_t n_pages, float* kbar_cache, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!k_pool || !page_table || !kbar_cache || first_page < 0 || n_pages < 0 || first_page + n_pages > p.n)
+    return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(k_pool) || !aligned16(kbar_cache)) return OOMB_ERR_INVALID_ARG;
+  p.page_table = page_table;
+  p.k_pool = k_pool;
+  hipError_t e = launch_page_means(p, desc->dtype == OOMB_BF16, first_page, n_pages, kbar_cache, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_pages, int32_t* sel_pages,
+                                 int32_t* sel_count, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!sel_pages || !sel_count || window_pages < 0) return OOMB_ERR_INVALID_ARG;
+  hipError_t e = launch_local_page_list(p, window_pages, sel_pages, sel_count, (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

@@ -241,14 +241,19 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
   if (tid == 0) sel_count[g] = k_eff + m;
 }
 
+hipError_t launch_page_score_cached(const Params& p, const float* qbar, const float* cache, float* scores, hipStream_t st);
+
+// kbar_cache != nullptr: the page means come from the cache instead of the keys
 template <typename T, int D>
-static void launch_scoring(const Params& p, float* A, float* qbar, float* scores, hipStream_t st) {
+static void launch_scoring(const Params& p, float* A, float* qbar, float* scores, const float* kbar_cache, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PER_BLOCK = 256 / LPR;
   const int units = p.Hq * p.m;
   { ProfScope prof_("qpool_partial", st); qpool_partial_kernel<T, D><<<dim3((units + PER_BLOCK - 1) / PER_BLOCK), dim3(256), 0, st>>>(p, A); }
   const float r = 1.0f / (float)((int64_t)p.C * p.G);
   { ProfScope prof_("qpool_final", st); qpool_final_kernel<<<dim3(p.Hkv), dim3(D), 0, st>>>(p, A, qbar, r); }
-  if (p.n_past > 0) {
+  if (kbar_cache) {
+    (void)launch_page_score_cached(p, qbar, kbar_cache, scores, st);
+  } else if (p.n_past > 0) {
     const float inv_p = 1.0f / (float)p.P;
     dim3 grid((unsigned)((p.n_past + PER_BLOCK - 1) / PER_BLOCK), p.Hkv);
     { ProfScope prof_("page_score", st); page_score_kernel<T, D><<<grid, dim3(256), 0, st>>>(p, qbar, scores, inv_p); }
@@ -265,7 +270,7 @@ size_t score_workspace_bytes(const Params& p) {
 
 // Returns hipSuccess or the launch error.  dtype_is_bf16 picks the element type.
 hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel,
-                             int32_t* sel_count, float* scores_out, void* ws, hipStream_t st) {
+                             int32_t* sel_count, float* scores_out, void* ws, const float* kbar_cache, hipStream_t st) {
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   char* w = (char*)ws;
   float* A = (float*)w;
@@ -275,11 +280,11 @@ hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32
   float* scores = scores_out ? scores_out : (float*)w;
 
   if (is_bf16) {
-    if (p.D == 128) launch_scoring<bf16_t, 128>(p, A, qbar, scores, st);
-    else launch_scoring<bf16_t, 64>(p, A, qbar, scores, st);
+    if (p.D == 128) launch_scoring<bf16_t, 128>(p, A, qbar, scores, kbar_cache, st);
+    else launch_scoring<bf16_t, 64>(p, A, qbar, scores, kbar_cache, st);
   } else {
-    if (p.D == 128) launch_scoring<float, 128>(p, A, qbar, scores, st);
-    else launch_scoring<float, 64>(p, A, qbar, scores, st);
+    if (p.D == 128) launch_scoring<float, 128>(p, A, qbar, scores, kbar_cache, st);
+    else launch_scoring<float, 64>(p, A, qbar, scores, kbar_cache, st);
   }
   static int lds_cap_bytes = 0;
   constexpr int WANT = 144 * 1024;
