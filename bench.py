@@ -60,11 +60,29 @@ def cpu_baseline(w, x, sample_tokens):
             "seconds": t2 - t0}
 
 
+def rocminfo_max_clock_mhz():
+    """Max shader clock of the first GPU agent as rocminfo prints it (None if it cannot be read)."""
+    try:
+        import subprocess
+        txt = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=20).stdout
+        gpu = txt.split("Device Type:             GPU")
+        if len(gpu) < 2:
+            return None
+        # the clock line precedes "Device Type" inside the agent block: search the block of that agent
+        block = txt[txt.rfind("*******", 0, txt.find("Device Type:             GPU")):]
+        for line in block.splitlines():
+            if "Max Clock Freq. (MHz)" in line:
+                return int(line.split(":")[1].strip())
+    except Exception:
+        return None
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="qwen_sparse_1m")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -139,14 +157,17 @@ def main():
         step(s)
     torch.cuda.synchronize()
     api.profile_reset()
-    api.profile_enable(True)
+    api.profile_enable(2)   # the timed region brackets only the four large kernels with events
     flops = 0.0
     kv_bytes = 0.0
     pairs_sum = 0
+    chunk_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
+        chunk_ev[s][0].record()
         N = step(s)
+        chunk_ev[s][1].record()
         pr = pairs_of(w, N)
         pairs_sum += pr
         flops += 14.0 * w.D * pr * w.Hq
@@ -162,6 +183,28 @@ def main():
     api.profile_enable(False)
     prof = api.profile_read()
     dt = t1 - t0
+    # one more pass of the same steps with every kernel bracketed, for the full per-kernel table
+    api.profile_reset()
+    api.profile_enable(1)
+    for s in range(args.steps):
+        step(s)
+    torch.cuda.synchronize()
+    api.profile_enable(False)
+    prof_all = api.profile_read()
+    per_chunk_ms = [a.elapsed_time(b) for a, b in chunk_ev]
+    # the same K-step sequence twice more (per-kernel timing off, gradient pools restored to zero
+    # in between): run-to-run spread and the minimum; `value` stays the first, contract-timed run
+    repeats_ms = [dt * 1e3 / args.steps]
+    for _ in range(2):
+        if x["dk_pool"] is not None:
+            x["dk_pool"].zero_()
+            x["dv_pool"].zero_()
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        for s in range(args.steps):
+            step(s)
+        torch.cuda.synchronize()
+        repeats_ms.append((time.perf_counter() - r0) * 1e3 / args.steps)
 
     # dominant kernel and its roofline
     name, (ms_tot, launches) = max(prof.items(), key=lambda kv: kv[1][0])
@@ -186,7 +229,9 @@ def main():
             f = line.split()
             if len(f) == 5 and f[0] == name and f[1] == "read_bytes" and f[3] == "write_bytes":
                 roof["traffic"] = int(f[2]) + int(f[4])
-    kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof.items()}
+    kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof_all.items()}
+    for k, v in prof.items():  # the large kernels: durations of the timed region itself
+        kernels[k] = {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]}
     # measured ceilings of this device (outside the timed region): an MFMA issue loop and a streaming copy
     cbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     ceil_mfma = api.calibrate(0, cbuf)
@@ -222,7 +267,9 @@ def main():
         "frac_mfma_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "kernels": kernels,
         "phases": phases,
-        "device": {"name": props.name, "compute_units": props.multi_processor_count},
+        "ms_per_step_runs": repeats_ms, "ms_per_step_min": min(repeats_ms), "ms_per_chunk": per_chunk_ms,
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "max_clock_mhz": rocminfo_max_clock_mhz()},
         "ceilings": {"mfma_bf16_tflops_measured": ceil_mfma, "copy_gbs_measured": ceil_copy,
                      "mfma_bf16_tflops_peak": MFMA_BF16_PEAK_TFLOPS, "hbm_gbs_peak": HBM_PEAK_GBS,
                      "value_frac_of_measured_mfma": flops / dt / 1e12 / ceil_mfma},

@@ -185,9 +185,11 @@ oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_page
 
 /*
  * Benchmark aid (not part of the paper's method): per-kernel device time.  While
- * enabled, every kernel the library launches is bracketed by two HIP events
+ * enabled (on = 1), every kernel the library launches is bracketed by two HIP events
  * recorded on the caller's stream (events are host objects created on demand; no
- * device memory is allocated).  oomb_profile_read waits for the recorded events of
+ * device memory is allocated).  on = 2 brackets only the four large kernels (page
+ * scoring, forward, dQ, dK/dV), which disturbs back-to-back launches less; on = 0
+ * switches the timing off.  oomb_profile_read waits for the recorded events of
  * entry idx (0 <= idx < oomb_profile_count()) and returns the kernel's name, its
  * accumulated device time in milliseconds and its launch count; it returns
  * OOMB_ERR_INVALID_ARG for a bad index or NULL outputs.  oomb_profile_reset drops

@@ -186,9 +186,10 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
     return d_q
 
 
-def profile_enable(on: bool) -> None:
-    """oomb_profile_enable: bracket every kernel launch with HIP events on the launch stream."""
-    lib().oomb_profile_enable(1 if on else 0)
+def profile_enable(on) -> None:
+    """oomb_profile_enable: 1 / True brackets every kernel launch with HIP events on the launch stream,
+    2 only the four large kernels, 0 / False none."""
+    lib().oomb_profile_enable(int(on))
 
 
 def profile_reset() -> None:

@@ -17,7 +17,7 @@ struct Entry {
   int64_t launches = 0;
 };
 std::mutex g_mu;
-bool g_on = false;
+int g_level = 0;  // 0 off, 1 every kernel, 2 only the four large kernels
 std::vector<Entry> g_entries;
 std::vector<hipEvent_t> g_free;
 
@@ -47,7 +47,10 @@ void drain(Entry& en) {
 }  // namespace
 
 ProfScope::ProfScope(const char* name, hipStream_t st) : stream_(st), slot_(-1), start_(nullptr) {
-  if (!g_on) return;
+  if (!g_level) return;
+  if (g_level == 2 && std::strcmp(name, "attn_fwd_mfma") && std::strcmp(name, "bwd_dq_mfma") &&
+      std::strcmp(name, "bwd_dkv_mfma") && std::strcmp(name, "page_score"))
+    return;
   std::lock_guard<std::mutex> lk(g_mu);
   for (size_t i = 0; i < g_entries.size(); ++i)
     if (g_entries[i].name == name) slot_ = (int)i;
@@ -75,7 +78,7 @@ extern "C" {
 
 void oomb_profile_enable(int32_t on) {
   std::lock_guard<std::mutex> lk(oomb::g_mu);
-  oomb::g_on = on != 0;
+  oomb::g_level = on;
 }
 
 void oomb_profile_reset(void) {
