@@ -81,6 +81,53 @@ def test_strided_views_are_honoured():
     pu.check("dV", pu.f32(xs["dv_pool"]), ref["dv_pool"], "f32")
 
 
+def test_strided_views_are_honoured_by_the_mfma_kernels():
+    """The same with bf16 tensors (MFMA kernels, page and row-space images, direct global -> LDS copies):
+    Q / O / dO / dQ rows and pool rows padded by 8 elements, bf16 gradient pool."""
+    w = Workload("bf16_strided", 14, 2, 128, 128, 256, 128 * 11, 3, "bf16", "bf16", 0.0884, extra_phys=2, seed=41)
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+
+    def widen(t, pad=8):
+        big = torch.zeros(t.shape[:-1] + (t.shape[-1] + pad,), dtype=t.dtype, device=t.device)
+        big[..., :t.shape[-1]] = t
+        return big[..., :t.shape[-1]]
+
+    xs = dict(x)
+    for k in ("q", "d_o", "k_pool", "v_pool", "dk_pool", "dv_pool"):
+        xs[k] = widen(x[k])
+        assert not xs[k].is_contiguous()
+    osel, ocnt, _ = pu.oracle_select(w, hx)
+    sel, cnt, _ = pu.gpu_select(w, xs)
+    torch.cuda.synchronize()
+    assert np.array_equal(sel.cpu().numpy(), osel)
+    desc = api.make_desc(xs["q"], xs["k_pool"], w.N, w.sm_scale, torch.bfloat16)
+    o = widen(torch.empty_like(x["q"]))
+    dq = widen(torch.empty_like(x["q"]))
+    o, lse = api.paged_attn_fwd(desc, xs["q"], xs["k_pool"], xs["v_pool"], xs["page_table"], sel, cnt, o=o)
+    api.paged_attn_bwd(desc, xs["q"], xs["k_pool"], xs["v_pool"], xs["page_table"], o, lse, xs["d_o"],
+                       xs["dk_pool"], xs["dv_pool"], sel, cnt, d_q=dq)
+    torch.cuda.synchronize()
+    ref = pu.oracle_fwd_bwd(w, hx, osel, ocnt)
+    pu.check("O", pu.f32(o), ref["o"], "bf16")
+    pu.check("dQ", pu.f32(dq), ref["dq"], "bf16")
+    pu.check("dK", pu.f32(xs["dk_pool"]), ref["dk_pool"], "bf16")
+    pu.check("dV", pu.f32(xs["dv_pool"]), ref["dv_pool"], "bf16")
+
+
+def test_mfma_backward_is_deterministic():
+    """bf16 path (sliced dK/dV with the fixed-order reduce): two runs give identical bits."""
+    w = WORKLOADS["mid_sparse_bf16"]
+    outs = []
+    for _ in range(2):
+        x = make_inputs(w, "cuda")
+        sel, cnt, _ = pu.gpu_select(w, x)
+        r = pu.gpu_fwd_bwd(w, x, sel, cnt)
+        outs.append({k: v.clone() for k, v in r.items()})
+    for k in outs[0]:
+        assert torch.equal(outs[0][k], outs[1][k]), k
+
+
 def test_backward_is_deterministic():
     """Page ownership instead of atomics: two runs give identical bits."""
     w = WORKLOADS["tiny_sparse"]
