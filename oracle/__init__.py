@@ -40,7 +40,8 @@ class _Desc(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("chunk_len", ctypes.c_int32), ("in_is_bf16", ctypes.c_int32),
-                ("ctx_len", ctypes.c_int64), ("sm_scale", ctypes.c_double)]
+                ("ctx_len", ctypes.c_int64), ("sm_scale", ctypes.c_double),
+                ("lists_per_query_page", ctypes.c_int32)]
 
 
 @dataclass
@@ -110,9 +111,9 @@ def _inputs(prec, *arrays):
     return 0, [np.ascontiguousarray(a, dtype=_real(prec)) for a in arrays]
 
 
-def _desc(sh: Shape, is_bf16: int) -> _Desc:
+def _desc(sh: Shape, is_bf16: int, per_query_page: int = 0) -> _Desc:
     assert sh.Hq % sh.Hkv == 0 and sh.C % sh.P == 0 and sh.N % sh.P == 0 and sh.N >= sh.C
-    return _Desc(sh.Hq, sh.Hkv, sh.D, sh.P, sh.C, is_bf16, sh.N, float(sh.sm_scale))
+    return _Desc(sh.Hq, sh.Hkv, sh.D, sh.P, sh.C, is_bf16, sh.N, float(sh.sm_scale), per_query_page)
 
 
 def _i32(a):
@@ -120,10 +121,14 @@ def _i32(a):
 
 
 def _sel_args(sel, sel_count):
+    """-> (sel, sel_count, row stride, lists per query page?).  A 2-d sel [Hkv][stride] is one list per
+    KV head; a 3-d sel [Hkv][m][stride] (sel_count [Hkv][m]) is one list per KV head and query page."""
     if sel is None:
-        return None, None, 0
+        return None, None, 0, 0
     sel = _i32(sel)
-    return sel, _i32(sel_count), int(sel.shape[1])
+    cnt = _i32(sel_count)
+    assert sel.ndim in (2, 3) and cnt.shape == sel.shape[:-1]
+    return sel, cnt, int(sel.shape[-1]), int(sel.ndim == 3)
 
 
 def page_score_topk(sh: Shape, q, k_pool, page_table, top_k: int):
@@ -182,6 +187,24 @@ def page_means(sh: Shape, k_pool, page_table, first: int, count: int, kbar_cache
     return kb
 
 
+def page_vote_topk(sh: Shape, q, kbar_cache, top_k: int, kbar_round_bf16=None):
+    """Retrieval by voting, one list per (KV head, query page): returns (sel [Hkv][m][top_k + m] int32
+    padded with -1, sel_count [Hkv][m], votes [Hkv][m][n_past] float64).  kbar_cache [>= n_past][Hkv][D]
+    float32 holds the page means; they are rounded to bf16 first when q is bf16 (or when
+    kbar_round_bf16 says so).  Double arithmetic."""
+    bf, (q,) = _inputs("f64", q)
+    kb = np.ascontiguousarray(kbar_cache, dtype=np.float32)
+    assert kb.shape[0] >= sh.n_past and kb.shape[1:] == (sh.Hkv, sh.D)
+    rnd = bf if kbar_round_bf16 is None else int(bool(kbar_round_bf16))
+    sel = np.full((sh.Hkv, sh.m, top_k + sh.m), -1, dtype=np.int32)
+    cnt = np.zeros((sh.Hkv, sh.m), dtype=np.int32)
+    votes = np.zeros((sh.Hkv, sh.m, max(sh.n_past, 0)), dtype=np.float64)
+    d = _desc(sh, bf)
+    _lib("f64").oomb_oracle_page_vote_topk(ctypes.byref(d), _ptr(q), _ptr(kb), ctypes.c_int32(rnd),
+                                           ctypes.c_int32(top_k), _ptr(sel), _ptr(cnt), _ptr(votes))
+    return sel, cnt, votes
+
+
 def local_page_list(sh: Shape, window_pages: int):
     """Page list of a local-attention layer: (sel [Hkv][window_pages + m] int32 padded with -1, sel_count)."""
     sel = np.full((sh.Hkv, window_pages + sh.m), -1, dtype=np.int32)
@@ -197,7 +220,7 @@ def attn_fwd(sh: Shape, q, k_pool, v_pool, page_table, sel=None, sel_count=None,
     is [n_rows][D] and LSE [n_rows]; otherwise O [C][Hq][D], LSE [Hq][C]."""
     bf, (q, k_pool, v_pool) = _inputs(prec, q, k_pool, v_pool)
     pt = _i32(page_table)
-    sel, cnt, stride = _sel_args(sel, sel_count)
+    sel, cnt, stride, qp = _sel_args(sel, sel_count)
     rt = _real(prec)
     if rows is None:
         o = np.zeros((sh.C, sh.Hq, sh.D), dtype=rt)
@@ -208,7 +231,7 @@ def attn_fwd(sh: Shape, q, k_pool, v_pool, page_table, sel=None, sel_count=None,
         nr = rows.shape[0]
         o = np.zeros((nr, sh.D), dtype=rt)
         lse = np.zeros((nr,), dtype=rt)
-    d = _desc(sh, bf)
+    d = _desc(sh, bf, qp)
     _lib(prec).oomb_oracle_attn_fwd(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
                                     _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(rows),
                                     ctypes.c_int64(nr), _ptr(o), _ptr(lse))
@@ -220,11 +243,11 @@ def row_probs(sh: Shape, q, k_pool, page_table, h: int, i: int, sel=None, sel_co
     """Softmax probabilities of row (h, i) and the token positions they belong to."""
     bf, (q, k_pool) = _inputs(prec, q, k_pool)
     pt = _i32(page_table)
-    sel, cnt, stride = _sel_args(sel, sel_count)
+    sel, cnt, stride, qp = _sel_args(sel, sel_count)
     cap = sh.N
     p = np.zeros(cap, dtype=_real(prec))
     tok = np.zeros(cap, dtype=np.int64)
-    d = _desc(sh, bf)
+    d = _desc(sh, bf, qp)
     nv = _lib(prec).oomb_oracle_row_probs(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(pt), _ptr(sel),
                                           _ptr(cnt), ctypes.c_int32(stride), ctypes.c_int32(h),
                                           ctypes.c_int32(i), _ptr(p), _ptr(tok))
@@ -246,7 +269,7 @@ def attn_bwd_dq(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, sel=
     """dQ ([C][Hq][D], or [n_rows][D] for a row subset).  lse/delta_ are [Hq][C]."""
     bf, (q, k_pool, v_pool, d_o) = _inputs(prec, q, k_pool, v_pool, d_o)
     pt = _i32(page_table)
-    sel, cnt, stride = _sel_args(sel, sel_count)
+    sel, cnt, stride, qp = _sel_args(sel, sel_count)
     rt = _real(prec)
     lse = np.ascontiguousarray(lse, dtype=rt)
     delta_ = np.ascontiguousarray(delta_, dtype=rt)
@@ -258,7 +281,7 @@ def attn_bwd_dq(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, sel=
         rows = _i32(rows).reshape(-1, 2)
         nr = rows.shape[0]
         dq = np.zeros((nr, sh.D), dtype=rt)
-    d = _desc(sh, bf)
+    d = _desc(sh, bf, qp)
     _lib(prec).oomb_oracle_attn_bwd_dq(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
                                        _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(lse),
                                        _ptr(delta_), _ptr(d_o), _ptr(rows), ctypes.c_int64(nr),
@@ -273,7 +296,7 @@ def attn_bwd_dkv(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, dk_
     page) pairs [n_units][2]; default every selected page of every KV head."""
     bf, (q, k_pool, v_pool, d_o) = _inputs(prec, q, k_pool, v_pool, d_o)
     pt = _i32(page_table)
-    sel, cnt, stride = _sel_args(sel, sel_count)
+    sel, cnt, stride, qp = _sel_args(sel, sel_count)
     rt = _real(prec)
     lse = np.ascontiguousarray(lse, dtype=rt)
     delta_ = np.ascontiguousarray(delta_, dtype=rt)
@@ -285,7 +308,7 @@ def attn_bwd_dkv(sh: Shape, q, k_pool, v_pool, page_table, lse, delta_, d_o, dk_
         units = _i32(units).reshape(-1, 2)
         nu = units.shape[0]
         assert len({(int(a), int(b)) for a, b in units}) == nu, "units must be distinct"
-    d = _desc(sh, bf)
+    d = _desc(sh, bf, qp)
     _lib(prec).oomb_oracle_attn_bwd_dkv(ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(pt),
                                         _ptr(sel), _ptr(cnt), ctypes.c_int32(stride), _ptr(lse),
                                         _ptr(delta_), _ptr(d_o), _ptr(units), ctypes.c_int64(nu),

@@ -17,6 +17,9 @@
  *   - Sec. 4.2: page-level sparse attention; each key page is represented by the
  *     mean of its keys, queries are aggregated into a score per key page, the
  *     top-K pages are kept and the same indices are reused by the backward pass.
+ *     Two aggregation rules: one pooled score and one list per KV head
+ *     (oomb_oracle_page_score_topk), and the section's own equation, softmax votes
+ *     summed per query page, one list per query page (oomb_oracle_page_vote_topk).
  *
  * Given a selection list, forward/backward are exactly masked softmax attention
  * and its exact gradient, so they are written as that definition.  The
@@ -68,6 +71,9 @@ typedef struct {
   int32_t in_is_bf16;  /* 1: Q,K,V,dO are uint16 bf16 bit patterns; 0: `real` */
   int64_t ctx_len;     /* N, includes the chunk, multiple of P */
   double sm_scale;     /* logits = sm_scale * <q, k> */
+  int32_t lists_per_query_page; /* 0: one page list per KV head, sel [Hkv][stride], sel_count [Hkv];
+                                   1: one list per (KV head, query page), sel [Hkv][m][stride],
+                                      sel_count [Hkv][m]: chunk row i uses the list of query page i / P */
 } oomb_oracle_desc;
 
 int oomb_oracle_real_bytes(void) { return (int)sizeof(real); }
@@ -89,16 +95,24 @@ static inline real ld(const void *base, int64_t idx, int is_bf16) {
   return ((const real *)base)[idx];
 }
 
-/* Selection list of KV head g: pointer + length.  sel == NULL means every
- * logical page 0..n-1 (dense). */
-static inline int32_t sel_len(const oomb_oracle_desc *d, const int32_t *sel_count, int g,
+/* Selection lists: list `lid` is that of KV head g (lid = g) or, with one list per query page
+ * (Sec. 4.2: the votes are aggregated for each of the m query pages), that of KV head g and query
+ * page tau (lid = g m + tau).  sel == NULL means every logical page 0..n-1 (dense). */
+static inline int list_id(const oomb_oracle_desc *d, int g, int i) {
+  if (!d->lists_per_query_page) return g;
+  return g * (d->chunk_len / d->page_size) + i / d->page_size;
+}
+static inline int n_lists(const oomb_oracle_desc *d) {
+  return d->lists_per_query_page ? d->n_kv_heads * (d->chunk_len / d->page_size) : d->n_kv_heads;
+}
+static inline int32_t sel_len(const oomb_oracle_desc *d, const int32_t *sel_count, int lid,
                               const int32_t *sel) {
   if (!sel) return (int32_t)(d->ctx_len / d->page_size);
-  return sel_count[g];
+  return sel_count[lid];
 }
-static inline int32_t sel_at(const int32_t *sel, int32_t sel_stride, int g, int32_t j) {
+static inline int32_t sel_at(const int32_t *sel, int32_t sel_stride, int lid, int32_t j) {
   if (!sel) return j;
-  return sel[(int64_t)g * sel_stride + j];
+  return sel[(int64_t)lid * sel_stride + j];
 }
 
 /* ------------------------------------------------------------------------- */
@@ -296,6 +310,114 @@ void oomb_oracle_local_page_list(const oomb_oracle_desc *d, int32_t window_pages
 }
 
 /* ------------------------------------------------------------------------- */
+/* Retrieval by voting (Sec. 4.2, the scoring equation): every query token scores all key pages
+ * against their representative vectors, turns the scores into a distribution over the key pages
+ * (softmax along the key-page index), and the distributions of the P tokens of a query page are
+ * summed into one vote per key page; each query page keeps its top-K pages.
+ *
+ * Written out, per KV head g, query page tau, past page l < n_past (all in double):
+ *   z[h][i][l]  = sm_scale * sum_d Q[i][h][d] * kbar[l][g][d]
+ *   p[h][i][.]  = softmax over l of z[h][i][.]
+ *   vote[g][tau][l] = sum over the G heads h of group g and the P tokens i of query page tau of p[h][i][l]
+ * The candidates are the past pages only; the order is larger vote first, then lower logical id;
+ * the first k_eff = min(top_k, n_past) are kept.  The list of query page tau is those pages
+ * followed by the local pages n_past .. n_past + tau (the ones its rows can see), ascending.
+ *
+ * kbar is read from kbar_cache [>= n_past][Hkv][D] (as written by oomb_oracle_page_means); with
+ * kbar_round_bf16 != 0 every element is first rounded to bf16 (nearest even), the precision in
+ * which a bf16 matrix instruction takes its operands.
+ *
+ * sel: [Hkv][m][top_k + m] (-1 padded), sel_count: [Hkv][m], votes: [Hkv][m][n_past] or NULL. */
+static double round_to_bf16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  float r;
+  memcpy(&r, &u, 4);
+  return (double)r;
+}
+
+typedef struct {
+  double s;
+  int32_t id;
+} vcand_t;
+
+static int vcand_cmp(const void *a, const void *b) {
+  const vcand_t *x = (const vcand_t *)a, *y = (const vcand_t *)b;
+  if (x->s > y->s) return -1;
+  if (x->s < y->s) return 1;
+  return (x->id > y->id) - (x->id < y->id);
+}
+
+void oomb_oracle_page_vote_topk(const oomb_oracle_desc *d, const void *Q, const float *kbar_cache,
+                                int32_t kbar_round_bf16, int32_t top_k, int32_t *sel, int32_t *sel_count,
+                                double *votes) {
+  const int Hq = d->n_q_heads, Hkv = d->n_kv_heads, D = d->head_dim, P = d->page_size;
+  const int C = d->chunk_len, G = Hq / Hkv, bf = d->in_is_bf16, m = C / P;
+  const int64_t n = d->ctx_len / P, n_past = n - m;
+  const int64_t k_eff = top_k < n_past ? top_k : n_past;
+  const int32_t stride = top_k + m;
+  const int64_t np1 = n_past > 0 ? n_past : 1;
+
+  double *kb = (double *)malloc(sizeof(double) * (size_t)np1 * D);
+  double *vote = (double *)malloc(sizeof(double) * (size_t)np1);
+  double *z = (double *)malloc(sizeof(double) * (size_t)np1);
+  vcand_t *cand = (vcand_t *)malloc(sizeof(vcand_t) * (size_t)np1);
+  char *keep = (char *)malloc((size_t)np1);
+
+  for (int g = 0; g < Hkv; ++g) {
+    for (int64_t l = 0; l < n_past; ++l)
+      for (int dd = 0; dd < D; ++dd) {
+        const float v = kbar_cache[((size_t)l * Hkv + g) * D + dd];
+        kb[l * D + dd] = kbar_round_bf16 ? round_to_bf16(v) : (double)v;
+      }
+    for (int tau = 0; tau < m; ++tau) {
+      for (int64_t l = 0; l < n_past; ++l) vote[l] = 0.0;
+      for (int h = g * G; h < g * G + G; ++h)
+        for (int i = tau * P; i < tau * P + P; ++i) {
+          double zmax = -INFINITY;
+          for (int64_t l = 0; l < n_past; ++l) {
+            double dot = 0.0;
+            for (int dd = 0; dd < D; ++dd)
+              dot += (double)ld(Q, ((int64_t)i * Hq + h) * D + dd, bf) * kb[l * D + dd];
+            z[l] = d->sm_scale * dot;
+            if (z[l] > zmax) zmax = z[l];
+          }
+          double sum = 0.0;
+          for (int64_t l = 0; l < n_past; ++l) {
+            z[l] = exp(z[l] - zmax);
+            sum += z[l];
+          }
+          for (int64_t l = 0; l < n_past; ++l) vote[l] += z[l] / sum;
+        }
+      for (int64_t l = 0; l < n_past; ++l) {
+        cand[l].s = vote[l];
+        cand[l].id = (int32_t)l;
+        if (votes) votes[((int64_t)g * m + tau) * n_past + l] = vote[l];
+      }
+      if (n_past > 0) {
+        qsort(cand, (size_t)n_past, sizeof(vcand_t), vcand_cmp);
+        memset(keep, 0, (size_t)n_past);
+        for (int64_t j = 0; j < k_eff; ++j) keep[cand[j].id] = 1;
+      }
+      int32_t *out = sel + ((int64_t)g * m + tau) * stride;
+      int32_t cnt = 0;
+      for (int64_t l = 0; l < n_past; ++l)
+        if (keep[l]) out[cnt++] = (int32_t)l;
+      for (int64_t l = n_past; l <= n_past + tau; ++l) out[cnt++] = (int32_t)l;
+      sel_count[g * m + tau] = cnt;
+      for (int32_t j = cnt; j < stride; ++j) out[j] = -1;
+    }
+  }
+  free(kb);
+  free(vote);
+  free(z);
+  free(cand);
+  free(keep);
+}
+
+/* ------------------------------------------------------------------------- */
 /* Logits of one query row against every visible token of the selected pages.
  * Returns the number of visible tokens; s[j] are the scaled logits, tok[j] the
  * token positions, in ascending token order. */
@@ -306,10 +428,11 @@ static int64_t row_logits(const oomb_oracle_desc *d, const void *Q, const void *
   const int G = Hq / Hkv, g = h / G, bf = d->in_is_bf16;
   const int64_t a_i = d->ctx_len - d->chunk_len + i;
   const real scale = (real)d->sm_scale;
-  const int32_t cnt = sel_len(d, sel_count, g, sel);
+  const int lid = list_id(d, g, i);
+  const int32_t cnt = sel_len(d, sel_count, lid, sel);
   int64_t nv = 0;
   for (int32_t j = 0; j < cnt; ++j) {
-    const int64_t l = sel_at(sel, sel_stride, g, j);
+    const int64_t l = sel_at(sel, sel_stride, lid, j);
     const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
     for (int t = 0; t < P; ++t) {
       const int64_t pos = l * P + t;
@@ -328,8 +451,8 @@ static int64_t row_logits(const oomb_oracle_desc *d, const void *Q, const void *
 
 static int64_t max_visible(const oomb_oracle_desc *d, const int32_t *sel, const int32_t *sel_count) {
   int64_t mx = 0;
-  for (int g = 0; g < d->n_kv_heads; ++g) {
-    int64_t c = sel_len(d, sel_count, g, sel);
+  for (int lid = 0; lid < n_lists(d); ++lid) {
+    int64_t c = sel_len(d, sel_count, lid, sel);
     if (c > mx) mx = c;
   }
   return mx * d->page_size;
@@ -467,10 +590,10 @@ void oomb_oracle_attn_bwd_dq(const oomb_oracle_desc *d, const void *Q, const voi
  * of KV head g:
  *   dV[t,g,:] += sum_{h in g} sum_{i : t visible} p_t(h,i) dO[i,h,:]
  *   dK[t,g,:] += sm_scale * sum_{h in g} sum_{i} ds_t(h,i) Q[i,h,:]
- * written at pool[page_table[t / P]][g][t % P][:].  Pages outside the list are
- * not touched.  units == NULL: every (g, selected page).  units != NULL:
- * n_units pairs (g, logical page); a listed page that is not selected for g
- * contributes nothing. */
+ * written at pool[page_table[t / P]][g][t % P][:], where the sums run over the rows whose
+ * list holds the page of t.  Pages outside every list are not touched.  units == NULL: every
+ * (g, page in some list of g).  units != NULL: n_units pairs (g, logical page); a listed page
+ * that is in no list of g contributes nothing. */
 void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const void *Kpool,
                               const void *Vpool, const int32_t *page_table, const int32_t *sel,
                               const int32_t *sel_count, int32_t sel_stride, const real *LSE,
@@ -481,7 +604,19 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
   const real scale = (real)d->sm_scale;
   const int64_t N = d->ctx_len;
 
-  /* flatten the work list */
+  /* member[(g n + l) n_tau + tau] = 1 iff logical page l is in the list that the rows of query page
+   * tau use for KV head g (with one list per KV head n_tau = 1: every row uses the same list) */
+  const int64_t n = N / P;
+  const int n_tau = d->lists_per_query_page ? C / P : 1;
+  char *member = (char *)calloc((size_t)Hkv * (size_t)n * (size_t)n_tau, 1);
+  for (int g = 0; g < Hkv; ++g)
+    for (int tau = 0; tau < n_tau; ++tau) {
+      const int lid = d->lists_per_query_page ? g * n_tau + tau : g;
+      for (int32_t j = 0; j < sel_len(d, sel_count, lid, sel); ++j)
+        member[((int64_t)g * n + sel_at(sel, sel_stride, lid, j)) * n_tau + tau] = 1;
+    }
+
+  /* flatten the work list: the given units, or every (g, page) that some list of g holds */
   int64_t total = 0;
   int32_t *work = NULL;
   if (units) {
@@ -489,14 +624,15 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
     work = (int32_t *)malloc(sizeof(int32_t) * 2 * (size_t)(total > 0 ? total : 1));
     memcpy(work, units, sizeof(int32_t) * 2 * (size_t)total);
   } else {
-    for (int g = 0; g < Hkv; ++g) total += sel_len(d, sel_count, g, sel);
-    work = (int32_t *)malloc(sizeof(int32_t) * 2 * (size_t)(total > 0 ? total : 1));
-    int64_t w = 0;
+    work = (int32_t *)malloc(sizeof(int32_t) * 2 * (size_t)Hkv * (size_t)n);
     for (int g = 0; g < Hkv; ++g)
-      for (int32_t j = 0; j < sel_len(d, sel_count, g, sel); ++j) {
-        work[2 * w] = g;
-        work[2 * w + 1] = sel_at(sel, sel_stride, g, j);
-        ++w;
+      for (int64_t l = 0; l < n; ++l) {
+        int any = 0;
+        for (int tau = 0; tau < n_tau; ++tau) any |= member[((int64_t)g * n + l) * n_tau + tau];
+        if (!any) continue;
+        work[2 * total] = g;
+        work[2 * total + 1] = (int32_t)l;
+        ++total;
       }
   }
 
@@ -504,9 +640,9 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
   for (int64_t u = 0; u < total; ++u) {
     const int g = work[2 * u];
     const int64_t l = work[2 * u + 1];
+    const char *mem = member + ((int64_t)g * n + l) * n_tau;
     int selected = 0;
-    for (int32_t j = 0; j < sel_len(d, sel_count, g, sel); ++j)
-      if (sel_at(sel, sel_stride, g, j) == l) selected = 1;
+    for (int tau = 0; tau < n_tau; ++tau) selected |= mem[tau];
     if (!selected) continue;
     const int64_t base = ((int64_t)page_table[l] * Hkv + g) * P * D;
     real *dk = (real *)malloc(sizeof(real) * (size_t)D);
@@ -518,6 +654,7 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
         for (int i = 0; i < C; ++i) {
           const int64_t a_i = N - C + i;
           if (pos > a_i) continue;
+          if (!mem[n_tau > 1 ? i / P : 0]) continue; /* the row's list does not hold this page */
           const int64_t qoff = ((int64_t)i * Hq + h) * D;
           real dot = 0, dp = 0;
 #pragma omp simd reduction(+ : dot)
@@ -542,4 +679,5 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
     free(dv);
   }
   free(work);
+  free(member);
 }
