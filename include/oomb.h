@@ -55,7 +55,14 @@ typedef enum {
 
 typedef enum { OOMB_F32 = 0, OOMB_BF16 = 1 } oomb_dtype;
 
-typedef enum { OOMB_OP_SCORE_TOPK = 0, OOMB_OP_ATTN_FWD = 1, OOMB_OP_ATTN_BWD = 2 } oomb_op;
+typedef enum {
+  OOMB_OP_SCORE_TOPK = 0,
+  OOMB_OP_ATTN_FWD = 1,
+  OOMB_OP_ATTN_BWD = 2,
+  OOMB_OP_VOTE_TOPK = 3,   /* oomb_page_vote_topk */
+  OOMB_OP_ATTN_FWD_QP = 4, /* oomb_paged_attn_fwd_qp */
+  OOMB_OP_ATTN_BWD_QP = 5  /* oomb_paged_attn_bwd_qp */
+} oomb_op;
 
 typedef struct {
   int32_t n_q_heads;   /* Hq */
@@ -73,10 +80,12 @@ typedef struct {
 } oomb_attn_desc;
 
 /* Bytes of device workspace `op` needs for this descriptor.  top_k: for
- * OOMB_OP_SCORE_TOPK the number of pages to retrieve; for OOMB_OP_ATTN_FWD and
- * OOMB_OP_ATTN_BWD the selection list's row stride minus the m local pages (i.e.
- * the top_k the list was built with), or a negative value for a dense call
- * (sel_pages == NULL).  Returns 0 for an invalid descriptor. */
+ * OOMB_OP_SCORE_TOPK and OOMB_OP_VOTE_TOPK the number of pages to retrieve; for
+ * OOMB_OP_ATTN_FWD and OOMB_OP_ATTN_BWD the selection list's row stride minus the m
+ * local pages (i.e. the top_k the list was built with), or a negative value for a
+ * dense call (sel_pages == NULL); for the _QP operations the lists' row stride minus
+ * m (>= 0).  The _QP sizes cover the worst case in which the lists of a KV head share
+ * no page (m * (top_k + m) distinct pages).  Returns 0 for an invalid descriptor. */
 size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t op);
 
 /*
@@ -143,6 +152,33 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
                                 int32_t sel_stride, const void* o, const float* lse,
                                 const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Attention with one page list per (KV head, query page) (Sec. 4.2: the votes are
+ * aggregated for each of the m query pages of the chunk, so every query page
+ * retrieves its own top-K key pages).  Same operators as oomb_paged_attn_fwd / _bwd,
+ * except that chunk row i of a head of KV head g sees token t iff t <= a_i and page
+ * t / P is in the list of (g, query page i / P):
+ *   sel_pages [Hkv][m][sel_stride] int32 logical page ids, ascending, distinct, in [0, n)
+ *   sel_count [Hkv][m]             valid entries of each list
+ * The list of query page tau must hold the local page n_past + tau (so that no row is
+ * empty); local pages beyond it may be listed and are ignored.  sel_stride >= m.
+ * dK / dV: every page that appears in some list of KV head g is updated by exactly one
+ * workgroup per slice of the query pages that list it, slices being added in a fixed
+ * order (no atomics on results; bit-reproducible); pages in no list are untouched.
+ * Workspace: oomb_workspace_bytes(desc, sel_stride - m, OOMB_OP_ATTN_FWD_QP / _BWD_QP).
+ */
+oomb_status oomb_paged_attn_fwd_qp(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* page_table,
+                                   const int32_t* sel_pages, const int32_t* sel_count,
+                                   int32_t sel_stride, void* o, float* lse, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+oomb_status oomb_paged_attn_bwd_qp(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* page_table,
+                                   const int32_t* sel_pages, const int32_t* sel_count,
+                                   int32_t sel_stride, const void* o, const float* lse,
+                                   const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Paged-manager steps either side of the attention path (Sec. 4.1: the KV cache

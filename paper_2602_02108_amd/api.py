@@ -14,12 +14,13 @@ LIB_PATH = os.path.join(_HERE, "liboomb.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
 F32, BF16 = 0, 1
-OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD = 0, 1, 2
+OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD, OP_VOTE_TOPK, OP_ATTN_FWD_QP, OP_ATTN_BWD_QP = range(6)
 
 EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
            "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
-           "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list"]
+           "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
+           "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -61,6 +62,10 @@ def lib():
         l.oomb_paged_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, u64, vp]
         l.oomb_paged_attn_bwd.restype = i32
         l.oomb_paged_attn_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+        l.oomb_paged_attn_fwd_qp.restype = i32
+        l.oomb_paged_attn_fwd_qp.argtypes = l.oomb_paged_attn_fwd.argtypes
+        l.oomb_paged_attn_bwd_qp.restype = i32
+        l.oomb_paged_attn_bwd_qp.argtypes = l.oomb_paged_attn_bwd.argtypes
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
@@ -183,6 +188,46 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
                                    _p(dk_pool), _p(dv_pool), _p(workspace), nbytes, _stream(q))
     if st != OK:
         raise OombError(st, "oomb_paged_attn_bwd")
+    return d_q
+
+
+def _qp_lists(desc, sel_pages, sel_count):
+    m = desc.chunk_len // desc.page_size
+    assert sel_pages.dim() == 3 and sel_pages.shape[:2] == (desc.n_kv_heads, m) and sel_pages.is_contiguous()
+    assert sel_count.shape == (desc.n_kv_heads, m) and sel_count.is_contiguous()
+    return int(sel_pages.shape[2]), m
+
+
+def paged_attn_fwd_qp(desc: AttnDesc, q, k_pool, v_pool, page_table, sel_pages, sel_count, o=None, lse=None,
+                      workspace=None):
+    """oomb_paged_attn_fwd_qp: one list per (KV head, query page), sel_pages [Hkv][m][stride] int32,
+    sel_count [Hkv][m].  Returns (O, LSE)."""
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((desc.n_q_heads, desc.chunk_len), dtype=torch.float32, device=q.device)
+    stride, m = _qp_lists(desc, sel_pages, sel_count)
+    workspace, nbytes = _workspace(desc, stride - m, OP_ATTN_FWD_QP, q.device, workspace)
+    st = lib().oomb_paged_attn_fwd_qp(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
+                                      _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(workspace), nbytes,
+                                      _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_paged_attn_fwd_qp")
+    return o, lse
+
+
+def paged_attn_bwd_qp(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, dk_pool, dv_pool, sel_pages,
+                      sel_count, d_q=None, workspace=None):
+    """oomb_paged_attn_bwd_qp.  Returns dQ; dk_pool / dv_pool are accumulated in place."""
+    if d_q is None:
+        d_q = torch.empty_like(q)
+    stride, m = _qp_lists(desc, sel_pages, sel_count)
+    workspace, nbytes = _workspace(desc, stride - m, OP_ATTN_BWD_QP, q.device, workspace)
+    st = lib().oomb_paged_attn_bwd_qp(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
+                                      _p(sel_pages), _p(sel_count), stride, _p(o), _p(lse), _p(d_o), _p(d_q),
+                                      _p(dk_pool), _p(dv_pool), _p(workspace), nbytes, _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_paged_attn_bwd_qp")
     return d_q
 
 

@@ -21,6 +21,9 @@ hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
 size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
+size_t qp_maps_bytes(const Params& p, int32_t stride);
+int32_t qp_union_cap(const Params& p, int32_t stride);
+hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st);
 }  // namespace oomb
 
 using namespace oomb;
@@ -87,6 +90,24 @@ oomb_status check_list(const Params& p, const int32_t* sel, const int32_t* cnt, 
   return OOMB_OK;
 }
 
+// One list per (KV head, query page): [maps derived from the lists][what the kernels need with the
+// union of a KV head's lists in the place of its list].  p.sel_stride is set here.
+size_t qp_workspace_bytes(Params p, int32_t stride, bool bf, bool bwd) {
+  p.qp = 1;
+  p.sel_stride = stride;
+  const size_t maps = qp_maps_bytes(p, stride);
+  const int32_t cap = qp_union_cap(p, stride);
+  if (!force_generic() && mfma_supported(p, bf))
+    return maps + (bwd ? bwd_mfma_workspace_bytes(p, cap) : fwd_mfma_workspace_bytes(p, cap));
+  return maps + (bwd ? up256((size_t)p.Hq * p.C * sizeof(float)) : 256);
+}
+
+oomb_status check_qp_list(const Params& p, const int32_t* sel, const int32_t* cnt, int32_t stride) {
+  if (!sel || !cnt || stride < p.m) return OOMB_ERR_INVALID_ARG;
+  if ((int64_t)stride * p.m > INT32_MAX) return OOMB_ERR_UNSUPPORTED;
+  return OOMB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -111,6 +132,13 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
       const size_t generic = up256((size_t)p.Hq * p.C * sizeof(float));
       const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? bwd_mfma_workspace_bytes(p, (int32_t)max_len) : 0;
       return generic > mfma ? generic : mfma;
+    }
+    case OOMB_OP_ATTN_FWD_QP:
+    case OOMB_OP_ATTN_BWD_QP: {
+      if (top_k < 0) return 0;
+      const int64_t stride = (int64_t)top_k + p.m;
+      if (stride * p.m > INT32_MAX) return 0;
+      return qp_workspace_bytes(p, (int32_t)stride, desc->dtype == OOMB_BF16, op == OOMB_OP_ATTN_BWD_QP);
     }
     default:
       return 0;
@@ -253,6 +281,77 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
     e = launch_delta(p, bf, st);
     if (e != hipSuccess) return OOMB_ERR_LAUNCH;
     e = launch_bwd_generic(p, bf, max_len, st);
+  }
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_paged_attn_fwd_qp(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* page_table,
+                                   const int32_t* sel_pages, const int32_t* sel_count,
+                                   int32_t sel_stride, void* o, float* lse, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !v_pool || !page_table || !o || !lse) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o)) return OOMB_ERR_INVALID_ARG;
+  s = check_qp_list(p, sel_pages, sel_count, sel_stride);
+  if (s != OOMB_OK) return s;
+  const bool bf = desc->dtype == OOMB_BF16;
+  if (!workspace || workspace_bytes < qp_workspace_bytes(p, sel_stride, bf, false) || !aligned16(workspace))
+    return OOMB_ERR_WORKSPACE;
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
+  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
+  p.o = o; p.lse = lse;
+  p.qp = 1;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e;
+  if (!force_generic() && mfma_supported(p, bf)) {
+    e = launch_qp_prepare(p, workspace, st);
+    if (e != hipSuccess) return OOMB_ERR_LAUNCH;
+    e = launch_fwd_mfma(p, qp_union_cap(p, sel_stride), (unsigned char*)workspace + qp_maps_bytes(p, sel_stride), st);
+  } else {
+    e = launch_fwd_generic(p, bf, st);
+  }
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_paged_attn_bwd_qp(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                   const void* v_pool, const int32_t* page_table,
+                                   const int32_t* sel_pages, const int32_t* sel_count,
+                                   int32_t sel_stride, const void* o, const float* lse,
+                                   const void* d_o, void* d_q, void* dk_pool, void* dv_pool,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !v_pool || !page_table || !o || !lse || !d_o || !d_q || !dk_pool || !dv_pool)
+    return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o) || !aligned16(d_o) ||
+      !aligned16(d_q) || !aligned16(dk_pool) || !aligned16(dv_pool))
+    return OOMB_ERR_INVALID_ARG;
+  s = check_qp_list(p, sel_pages, sel_count, sel_stride);
+  if (s != OOMB_OK) return s;
+  const bool bf = desc->dtype == OOMB_BF16;
+  const bool use_mfma = !force_generic() && mfma_supported(p, bf);
+  if (!workspace || workspace_bytes < qp_workspace_bytes(p, sel_stride, bf, true) || !aligned16(workspace))
+    return OOMB_ERR_WORKSPACE;
+  p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
+  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
+  p.o = const_cast<void*>(o); p.lse = const_cast<float*>(lse); p.d_o = d_o; p.d_q = d_q;
+  p.dk_pool = dk_pool; p.dv_pool = dv_pool;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = launch_qp_prepare(p, workspace, st);
+  if (e != hipSuccess) return OOMB_ERR_LAUNCH;
+  unsigned char* rest = (unsigned char*)workspace + qp_maps_bytes(p, sel_stride);
+  const int32_t cap = qp_union_cap(p, sel_stride);
+  if (use_mfma) {
+    e = launch_bwd_mfma(p, cap, rest, st);
+  } else {
+    p.delta = (float*)rest;
+    e = launch_delta(p, bf, st);
+    if (e != hipSuccess) return OOMB_ERR_LAUNCH;
+    e = launch_bwd_generic(p, bf, cap, st);
   }
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }

@@ -88,11 +88,24 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
     g = blockIdx.x % p.Hkv;
     unit = blockIdx.x / p.Hkv;
   }
-  const int32_t j = unit / n_split, sp = unit % n_split;
-  if (j >= max_len || j >= list_len(p, g)) return;
+  // one list per KV head: unit = (list entry, one of n_split equal slices of the rows that see it).
+  // one list per query page: unit = entry of the work table built with the inverse lists: a page of
+  // the union list and up to 8 of the query pages whose list holds it.
+  int32_t j, sp = 0, q0 = 0, qc = 0, pslot = -1;
+  if (p.qp) {
+    const int32_t n_units = p.unit_count[g];
+    if (unit >= n_units) return;
+    // (the table is in ascending page order; the chunk's own pages, seen by the most rows, come last: start them first)
+    const int4 un = p.units[(int64_t)g * p.max_units + (n_units - 1 - unit)];
+    j = un.x; q0 = un.y; qc = un.z; pslot = un.w;
+  } else {
+    j = unit / n_split;
+    sp = unit % n_split;
+    if (j >= max_len || j >= list_len(p, g)) return;
+  }
 
   const int64_t first_q = p.N - p.C;
-  const int64_t l = list_at(p, g, j);
+  const int64_t l = owned_at(p, g, j);
   const int64_t first = l * TP;
   const int64_t pool_off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
   const float c = p.sm_scale * 1.4426950408889634f;
@@ -113,9 +126,28 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   const int32_t nblk_all = (p.C / 32) * p.G;
   const int32_t st_lo_all = ((i_min / 32) * p.G) >> 1, st_hi_all = nblk_all >> 1;
   const int32_t st_cnt = st_hi_all - st_lo_all;
-  const int32_t s0 = st_lo_all + (int32_t)(((int64_t)st_cnt * sp) / n_split);
-  const int32_t s1 = st_lo_all + (int32_t)(((int64_t)st_cnt * (sp + 1)) / n_split);
+  // stage counter range [s0, s1).  One list per KV head: the stages themselves.  One list per query
+  // page: stage v of the unit is stage v % spq of query page tau[v / spq] (spq stages per query page)
+  const int32_t spq = (p.P / 32) * p.G / 2;
+  const int32_t s0 = p.qp ? 0 : st_lo_all + (int32_t)(((int64_t)st_cnt * sp) / n_split);
+  const int32_t s1 = p.qp ? qc * spq : st_lo_all + (int32_t)(((int64_t)st_cnt * (sp + 1)) / n_split);
   const int32_t nb = 2 * (s1 - s0);  // blocks of 32 rows
+  int32_t tau_v = 0;                 // lane k: k-th query page of this unit
+  if (p.qp && lane < qc)
+    tau_v = p.inv_qp[(int64_t)g * p.m * p.sel_stride + p.inv_off[(int64_t)g * (p.un_stride + 1) + j] + q0 + lane];
+  // walking the stages in order: real stage index of the current counter value and of the next one
+  int32_t walk_q = 0, walk_r = 0;
+  auto real_first = [&]() __attribute__((always_inline)) -> int32_t {
+    return p.qp ? __builtin_amdgcn_readlane(tau_v, 0) * spq : s0;
+  };
+  auto real_next = [&](const int32_t cur) __attribute__((always_inline)) -> int32_t {
+    if (!p.qp) return cur + 1;
+    if (++walk_r == spq) {
+      walk_r = 0;
+      ++walk_q;
+    }
+    return __builtin_amdgcn_readlane(tau_v, walk_q & 63) * spq + walk_r;  // (past the unit's end: unused)
+  };
   // offset of this lane's key behind the first chunk token; a row (chunk token i) sees the key iff i >= key_rel
   const int32_t key_rel = (int32_t)(first + 32 * kbw + lq - first_q);
 
@@ -194,9 +226,10 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + (xo + k * 1024)) = z;
     }
   }
+  int32_t rs = real_first();  // real stage of the stage being computed
   if (nb > 0) {
-    copy_natural(s0, 0);
-    copy_transposed(s0, 0);
+    copy_natural(rs, 0);
+    copy_transposed(rs, 0);
   }
   wait_copies<0>();
   __syncthreads();
@@ -291,15 +324,18 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         *reinterpret_cast<uint4*>(smem + (xo + half * 2048)) = p0;
         *reinterpret_cast<uint4*>(smem + (xo + (half * 2048 + 1024))) = p1;
       };
+      // s: stage counter; rs: its real stage; the next real stage is copied meanwhile
       auto stage0 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) copy_natural(s + 1, st ^ 1);
+        const int32_t rn = real_next(rs);
+        if (more) copy_natural(rn, st ^ 1);
         const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
-        step0(st, 0, 2 * s, st_a);
+        step0(st, 0, 2 * rs, st_a);
         mid_barrier(more);
-        if (more) copy_transposed(s + 1, st ^ 1);
-        step0(st, 1, 2 * s + 1, st_b);
+        if (more) copy_transposed(rn, st ^ 1);
+        step0(st, 1, 2 * rs + 1, st_b);
         end_barrier();
+        rs = rn;
       };
       for (int32_t s = s0; s < s1; s += 2) {
         stage0(s, 0);
@@ -331,13 +367,15 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
       auto stage1 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
         const bool more = s + 1 < s1;
-        if (more) copy_natural(s + 1, st ^ 1);
+        const int32_t rn = real_next(rs);
+        if (more) copy_natural(rn, st ^ 1);
         const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
         step1(st, 0, dpb, dpa, st_a);
         mid_barrier(more);
-        if (more) copy_transposed(s + 1, st ^ 1);
+        if (more) copy_transposed(rn, st ^ 1);
         step1(st, 1, dpa, dpb, st_b);
         end_barrier();
+        rs = rn;
       };
       for (int32_t s = s0; s < s1; s += 2) {
         stage1(s, 0);
@@ -361,9 +399,11 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 
   // epilogue: role 0 holds dV^T, role 1 holds dK^T (to be scaled), lane = key, 4 consecutive dims per group
   const float scale = role == 0 ? 1.f : p.sm_scale;
-  if (partial) {
-    float* dst = partial + ((((int64_t)g * max_len + j) * n_split + sp) * 2 + (role == 0 ? 1 : 0)) * (TP * HD) +
-                 (int64_t)(32 * kbw + lq) * HD;
+  // slices of a page go to fp32 partial pages (added to the pool by the reduce kernel), whole pages
+  // straight into the pool
+  const int64_t part_idx = p.qp ? (int64_t)pslot : (partial ? ((int64_t)g * max_len + j) * n_split + sp : -1);
+  if (part_idx >= 0) {
+    float* dst = partial + (part_idx * 2 + (role == 0 ? 1 : 0)) * (TP * HD) + (int64_t)(32 * kbw + lq) * HD;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -389,24 +429,32 @@ __global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(Params p, const flo
                                                              int32_t max_len, int32_t n_split) {
   const int g = blockIdx.z;
   const int32_t j = blockIdx.y;
-  if (j >= list_len(p, g)) return;
+  if (j >= owned_len(p, g)) return;
+  int64_t first_part = ((int64_t)g * max_len + j) * n_split;
+  if (p.qp) {  // only pages that were cut into several units have partial pages
+    n_split = p.un_ns[(int64_t)g * p.un_stride + j];
+    if (n_split <= 1) return;
+    first_part = p.un_pbase[(int64_t)g * p.un_stride + j];
+  }
   const int which = blockIdx.x >> 4;                       // 0: dK, 1: dV
   const int e4 = ((blockIdx.x & 15) * 256 + threadIdx.x);  // float4 index inside the 128 x 128 page
   const int key = e4 >> 5, d4 = (e4 & 31) * 4;
-  const int64_t l = list_at(p, g, j);
+  const int64_t l = owned_at(p, g, j);
   const int64_t pool_off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
                            (int64_t)key * p.pool_tok_stride + d4;
   float4 s = {0.f, 0.f, 0.f, 0.f};
   for (int sp = 0; sp < n_split; ++sp) {
-    const float4 v = *reinterpret_cast<const float4*>(
-        partial + ((((int64_t)g * max_len + j) * n_split + sp) * 2 + which) * (TP * HD) + key * HD + d4);
+    const float4 v = *reinterpret_cast<const float4*>(partial + ((first_part + sp) * 2 + which) * (TP * HD) + key * HD + d4);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   TG* pool = (TG*)(which == 0 ? p.dk_pool : p.dv_pool) + pool_off;
   kv_rmw4<TG>(pool, s.x, s.y, s.z, s.w);
 }
 
+int32_t qp_max_pslots(const Params& p, int32_t stride);
+
 size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split) {
+  if (p.qp) return (size_t)p.Hkv * (size_t)qp_max_pslots(p, p.sel_stride) * 2 * TP * HD * sizeof(float);
   if (n_split <= 1) return 0;
   return (size_t)p.Hkv * (size_t)max_len * (size_t)n_split * 2 * TP * HD * sizeof(float);
 }
@@ -430,11 +478,12 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int32_t n_split = dkv_splits(p, max_len);
-  float* partial = n_split > 1 ? partial_ws : nullptr;
+  // (one list per query page: the units come from the device-built table; the grid covers its capacity)
+  const int32_t n_split = p.qp ? 1 : dkv_splits(p, max_len);
+  float* partial = (p.qp || n_split > 1) ? partial_ws : nullptr;
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
   const int per = xcd_map ? 8 / p.Hkv : 1;
-  const int64_t units = (int64_t)max_len * n_split;
+  const int64_t units = p.qp ? (int64_t)p.max_units : (int64_t)max_len * n_split;
   const unsigned blocks = xcd_map ? 8u * (unsigned)((units + per - 1) / per) : (unsigned)units * p.Hkv;
   {
     ProfScope prof_("bwd_dkv_mfma", st);
@@ -447,7 +496,7 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (n_split > 1) {
+  if (p.qp || n_split > 1) {
     ProfScope prof_("bwd_dkv_reduce", st);
     dim3 grid(32, (unsigned)max_len, (unsigned)p.Hkv);
     if (p.grad_is_bf16) bwd_dkv_reduce_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(p, partial, max_len, n_split);

@@ -99,31 +99,29 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   if (tile >= tiles_per_head) return;
   tile = tiles_per_head - 1 - tile;
 
-  // row space: block b = tb * G + hd holds tokens 32 tb .. 32 tb + 31 of head g G + hd;
-  // wave w of tile t owns block 8 t + w
-  const int32_t nblk = (p.C / 32) * p.G;
+  // this wave's block of the row space (one head, 32 consecutive tokens) and the tile's page list
+  const RowTile rt = row_tile(p, g, tile, wave);
+  const int lid = rt.lid;
   const int64_t first_q = p.N - p.C;
-  const int32_t b_raw = tile * (DQ_ROWS / 32) + wave;
-  const bool r_valid = b_raw < nblk;                       // wave-uniform
-  const uint32_t bw = (uint32_t)(r_valid ? b_raw : nblk - 1);
+  const bool r_valid = rt.valid;                           // wave-uniform
+  const uint32_t bw = rt.bw;
   const uint32_t tbw = div_g(p, bw);
   const int i = (int)(32 * tbw + lq), h = g * p.G + (int)(bw - tbw * p.G);
   const int64_t r = (int64_t)32 * bw + lq;                 // index into the row-space statistics
   const int64_t a_i = first_q + i;
-  const int64_t a_wave_min = first_q + 32 * tbw, a_wave_max = a_wave_min + 31;
-  const int32_t b_last = (tile * (DQ_ROWS / 32) + 7 < nblk) ? tile * (DQ_ROWS / 32) + 7 : nblk - 1;
-  const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)b_last) + 31;
+  const int64_t a_wave_max = first_q + 32 * tbw + 31;
+  const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)rt.b_last) + 31;
 
-  const int32_t T = visible_len(p, g, a_blk_max / TP, lane);
+  const int32_t T = visible_len(p, lid, a_blk_max / TP, lane);
   PageWindow pw;
-  pw.init(p, g, T, lane);
+  pw.init(p, lid, T, lane);
   int32_t T2 = 2 * T;
-  if (T > 0 && (int64_t)list_at(p, g, T - 1) * TP + 64 > a_blk_max) T2 -= 1;  // second half of the last page unseen
+  if (T > 0 && (int64_t)list_at(p, lid, T - 1) * TP + 64 > a_blk_max) T2 -= 1;  // second half of the last page unseen
   // half tiles [0, T_full) are seen in full by every row of the workgroup
   int32_t T_full = 0;
   {
-    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)(tile * (DQ_ROWS / 32)));
-    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, g, (a_blk_min - (TP - 1)) / TP, lane);
+    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)rt.b_first);
+    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, lid, (a_blk_min - (TP - 1)) / TP, lane);
     if (T_full > T2) T_full = T2;
   }
 
@@ -168,10 +166,13 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
     copy_kib_to_lds<2>(src, cp_off, lds_dst + 2048 * wave);
   };
+  // (image index of a half tile: its list position, or with one list per query page the page's
+  // position in the KV head's union list)
   auto copy_stage = [&](const int32_t ht, const int st) __attribute__((always_inline)) {
-    copy_tile(kn_img + (size_t)ht * 16384, st * 32768);
-    copy_tile(vn_img + (size_t)ht * 16384, st * 32768 + 16384);
-    copy_tile(kt_img + (size_t)ht * 16384, DQ_KT + st * 16384);
+    const size_t o = (size_t)(p.qp ? 2 * pw.phys(ht >> 1) + (ht & 1) : ht) * 16384;
+    copy_tile(kn_img + o, st * 32768);
+    copy_tile(vn_img + o, st * 32768 + 16384);
+    copy_tile(kt_img + o, DQ_KT + st * 16384);
   };
   auto copies_landed = [&]() __attribute__((always_inline)) { wait_copies<0>(); };
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   // st = t mod 2 is a compile-time constant: the loops are unrolled by two.  The copy of the next
   // half tile goes to the other stage, whose readers finished before the last barrier.
   auto iteration = [&](const int32_t t, const int st, const bool general) __attribute__((always_inline)) {
-    pw.advance(p, g, T, t >> 1, lane);
+    pw.advance(p, lid, T, t >> 1, lane);
     if (t + 1 < T2) copy_stage(t + 1, st ^ 1);
     if (!general) {
       half_tile(st, false, 0);
@@ -388,7 +389,7 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
   const int per = xcd_map ? 8 / p.Hkv : 1;
   {
-    const int tiles = (int)(((int64_t)p.C * p.G + DQ_ROWS - 1) / DQ_ROWS);
+    const int tiles = row_tiles_per_head(p.C, p.G, p.m, p.qp);
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
     hipError_t e = launch_kv_layout(p, max_list_len, DQ_IMG_KINDS, kv_img, st);
     if (e != hipSuccess) return e;

@@ -50,27 +50,24 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   if (tile >= tiles_per_head) return;
   tile = tiles_per_head - 1 - tile;  // rows late in the chunk see more local pages: start them first
 
-  // row space: block b = tb * G + hd holds tokens 32 tb .. 32 tb + 31 of head g G + hd;
-  // wave w of tile t owns block 8 t + w (one head, 32 consecutive tokens)
-  const int32_t nblk = (p.C / 32) * p.G;
+  // this wave's block of the row space (one head, 32 consecutive tokens) and the tile's page list
+  const RowTile rt = row_tile(p, g, tile, wave);
+  const int lid = rt.lid;
   const int64_t first_q = p.N - p.C;
-  const int32_t b_raw = tile * (FW_ROWS / 32) + wave;
-  const bool r_valid = b_raw < nblk;                       // wave-uniform
-  const uint32_t bw = (uint32_t)(r_valid ? b_raw : nblk - 1);
+  const bool r_valid = rt.valid;                           // wave-uniform
+  const uint32_t bw = rt.bw;
   const uint32_t tbw = div_g(p, bw);
   const uint32_t i = 32 * tbw + lq;
   const int h = g * p.G + (int)(bw - tbw * p.G);
   const int64_t a_i = first_q + i;
-  const int64_t a_wave_min = first_q + 32 * tbw, a_wave_max = a_wave_min + 31;
-  const int32_t b_last = (tile * (FW_ROWS / 32) + 7 < nblk) ? tile * (FW_ROWS / 32) + 7 : nblk - 1;
-  const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)b_last) + 31;
+  const int64_t a_blk_max = first_q + 32 * div_g(p, (uint32_t)rt.b_last) + 31;
 
   // number of half tiles visible to this workgroup (lists are ascending)
-  const int32_t T = visible_len(p, g, a_blk_max / TP, lane);
+  const int32_t T = visible_len(p, lid, a_blk_max / TP, lane);
   PageWindow pw;
-  pw.init(p, g, T, lane);
+  pw.init(p, lid, T, lane);
   int32_t T2 = 2 * T;
-  if (T > 0 && (int64_t)list_at(p, g, T - 1) * TP + HT > a_blk_max) T2 -= 1;  // second half of the last page unseen
+  if (T > 0 && (int64_t)list_at(p, lid, T - 1) * TP + HT > a_blk_max) T2 -= 1;  // second half of the last page unseen
 
   const bf16_t* qrow = (const bf16_t*)p.q + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
   bf16x8 qf[8];
@@ -119,8 +116,13 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
     copy_kib_to_lds<2>(src, cp_off, lds_dst + 2048 * wave);
   };
-  auto copy_k = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(k_img_g + (size_t)ht * 16384, KB + buf * HT_BYTES); };
-  auto copy_v = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(vt_img_g + (size_t)ht * 16384, buf * HT_BYTES); };
+  // image index of half tile ht of the list: the list position itself, or (one list per query page) the
+  // page's position in the KV head's union list, whose images are shared by all query pages
+  auto img_ht = [&](int32_t ht) __attribute__((always_inline)) -> size_t {
+    return (size_t)(p.qp ? 2 * pw.phys(ht >> 1) + (ht & 1) : ht) * 16384;
+  };
+  auto copy_k = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(k_img_g + img_ht(ht), KB + buf * HT_BYTES); };
+  auto copy_v = [&](int32_t ht, const int buf) __attribute__((always_inline)) { copy_tile(vt_img_g + img_ht(ht), buf * HT_BYTES); };
   auto copies_landed = [&]() __attribute__((always_inline)) { wait_copies<0>(); };
 
   // ---- the software pipeline -------------------------------------------------------
@@ -234,8 +236,8 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   // softmax unit lies in them need no mask.
   int32_t T_full = 0;
   {
-    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)(tile * (FW_ROWS / 32)));
-    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, g, (a_blk_min - (TP - 1)) / TP, lane);
+    const int64_t a_blk_min = first_q + 32 * (int64_t)div_g(p, (uint32_t)rt.b_first);
+    if (a_blk_min >= TP - 1) T_full = 2 * visible_len(p, lid, (a_blk_min - (TP - 1)) / TP, lane);
     if (T_full > T2) T_full = T2;
   }
 
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   auto iteration = [&](const int32_t t, const int r, const bool general) __attribute__((always_inline)) {
     const int kc = ((r + 1) % 3) * HT_BYTES, kw = ((r + 2) % 3) * HT_BYTES;
     const int vc = r * HT_BYTES, vw = ((r + 1) % 3) * HT_BYTES;
-    pw.advance(p, g, T, t >> 1, lane);
+    pw.advance(p, lid, T, t >> 1, lane);
     int relA = 0, relB = 0;
     if (general) {
       relA = rel_of(ht_first(t) + 32);
@@ -327,8 +329,7 @@ hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int64_t rows = (int64_t)p.C * p.G;
-  const int tiles = (int)((rows + FW_ROWS - 1) / FW_ROWS);
+  const int tiles = row_tiles_per_head(p.C, p.G, p.m, p.qp);
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
   unsigned blocks;
   if (xcd_map) {

@@ -52,9 +52,10 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void fwd_generic_kernel(Params p) {
   __builtin_amdgcn_wave_barrier();
 
   float m_run = -INFINITY, l_run = 0.f, oacc[GEN_MAX_D / 64] = {0.f, 0.f};
-  const int32_t len = list_len(p, g);
+  const int lid = list_id(p, g, i);
+  const int32_t len = list_len(p, lid);
   for (int32_t j = 0; j < len; ++j) {
-    const int64_t l = list_at(p, g, j);
+    const int64_t l = list_at(p, lid, j);
     const int64_t first = l * P;
     if (first > a_i) break;
     const int vis = (int)((a_i - first + 1 < P) ? (a_i - first + 1) : P);
@@ -127,9 +128,10 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void dq_generic_kernel(Params p) {
   __builtin_amdgcn_wave_barrier();
   const float lse = p.lse[(int64_t)h * p.C + i], delta = p.delta[(int64_t)h * p.C + i];
   float acc[GEN_MAX_D / 64] = {0.f, 0.f};
-  const int32_t len = list_len(p, g);
+  const int lid = list_id(p, g, i);
+  const int32_t len = list_len(p, lid);
   for (int32_t j = 0; j < len; ++j) {
-    const int64_t l = list_at(p, g, j);
+    const int64_t l = list_at(p, lid, j);
     const int64_t first = l * P;
     if (first > a_i) break;
     const int vis = (int)((a_i - first + 1 < P) ? (a_i - first + 1) : P);
@@ -178,9 +180,9 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void dkv_generic_kernel(Params p) {
   const int g = blockIdx.z;
   const int32_t j = blockIdx.y;
   const int t = blockIdx.x * GEN_WAVES + w;
-  if (j >= list_len(p, g) || t >= p.P) return;
+  if (j >= owned_len(p, g) || t >= p.P) return;
   const int D = p.D;
-  const int64_t l = list_at(p, g, j);
+  const int64_t l = owned_at(p, g, j);
   const int64_t pos = l * p.P + t;
   const int64_t koff = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
                        (int64_t)t * p.pool_tok_stride;
@@ -191,13 +193,33 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void dkv_generic_kernel(Params p) {
   __builtin_amdgcn_wave_barrier();
   const int64_t first_q = p.N - p.C;
   const int i_min = (int)(pos > first_q ? pos - first_q : 0);
-  const int64_t n_rows = (int64_t)(p.C - i_min) * p.G;
+  // rows that may see the token.  One list per KV head: every (token >= i_min, head of the group).
+  // One list per query page: the rows of the query pages in the page's inverse list.
+  const int32_t* inv = nullptr;
+  int32_t inv_cnt = 0;
+  if (p.qp) {
+    const int32_t* off = p.inv_off + (int64_t)g * (p.un_stride + 1) + j;
+    inv = p.inv_qp + (int64_t)g * p.m * p.sel_stride + off[0];
+    inv_cnt = off[1] - off[0];
+  }
+  const int64_t n_rows = p.qp ? (int64_t)inv_cnt * p.P * p.G : (int64_t)(p.C - i_min) * p.G;
+  auto row_of = [&](int64_t rr, int& i, int& h) -> bool {
+    if (!p.qp) {
+      i = i_min + (int)(rr / p.G);
+      h = g * p.G + (int)(rr % p.G);
+      return true;
+    }
+    const int32_t pg = p.P * p.G, q = (int32_t)(rr / pg), rem = (int32_t)(rr % pg);
+    i = inv[q] * p.P + rem / p.G;
+    h = g * p.G + rem % p.G;
+    return i >= i_min;
+  };
   float dk[GEN_MAX_D / 64] = {0.f, 0.f}, dv[GEN_MAX_D / 64] = {0.f, 0.f};
   for (int64_t r0 = 0; r0 < n_rows; r0 += 64) {
     const int64_t rr = r0 + lane;
     float pr = 0.f, ds = 0.f;
-    if (rr < n_rows) {
-      const int i = i_min + (int)(rr / p.G), h = g * p.G + (int)(rr % p.G);
+    int i = 0, h = 0;
+    if (rr < n_rows && row_of(rr, i, h)) {
       const int64_t roff = (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
       float dot = 0.f, dp = 0.f;
       for (int d = 0; d < D; ++d) {
@@ -212,9 +234,9 @@ __global__ __launch_bounds__(64 * GEN_WAVES) void dkv_generic_kernel(Params p) {
     __builtin_amdgcn_wave_barrier();
     const int cnt = (int)((n_rows - r0 < 64) ? (n_rows - r0) : 64);
     for (int x = 0; x < cnt; ++x) {
-      const int64_t r2 = r0 + x;
-      const int i = i_min + (int)(r2 / p.G), h = g * p.G + (int)(r2 % p.G);
-      const int64_t roff = (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
+      int i2 = 0, h2 = 0;
+      if (!row_of(r0 + x, i2, h2)) continue;  // (wave-uniform)
+      const int64_t roff = (int64_t)i2 * p.q_tok_stride + (int64_t)h2 * p.q_head_stride;
       const float a = pb[w][x], b = dsb[w][x];
 #pragma unroll
       for (int k = 0; k < GEN_MAX_D / 64; ++k) {

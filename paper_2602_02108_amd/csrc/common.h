@@ -30,6 +30,22 @@ struct Params {
   float* delta;              // [Hq][C], workspace
   int32_t grad_is_bf16;
   uint32_t g_magic;          // ceil(2^32 / G): row / G == umulhi(row, g_magic) for row < 2^32 / G, G > 1
+  // One page list per (KV head, query page) (Sec. 4.2, retrieval by votes): sel is [Hkv][m][sel_stride],
+  // sel_count [Hkv][m]; list id = g * m + query page.  The maps below are built on the device by
+  // qp_prepare from the lists, in the caller's workspace.
+  int32_t qp;                // 0: one list per KV head (list id = g)
+  int32_t un_stride;         // row stride of un_list / un_pbase / un_ns; inv_off rows are un_stride + 1 long
+  int32_t max_units;         // row stride of units
+  const int32_t* qp_slot;    // [Hkv][m][sel_stride]: position of each list entry in the union list
+  const int32_t* un_list;    // [Hkv][un_stride]: union of the lists of a KV head, ascending ("owned" pages)
+  const int32_t* un_count;   // [Hkv]
+  const int32_t* inv_off;    // [Hkv][un_stride + 1]: CSR offsets into inv_qp
+  const int32_t* inv_qp;     // [Hkv][m * sel_stride]: the query pages whose list holds a union entry, ascending
+  const int4* units;         // [Hkv][max_units] dK/dV work units: (union entry, first inverse-list index,
+                             //   number of query pages, partial slot or -1 = straight into the pool)
+  const int32_t* unit_count; // [Hkv]
+  const int32_t* un_pbase;   // [Hkv][un_stride]: first partial slot of a union entry cut into slices, else -1
+  const int32_t* un_ns;      // [Hkv][un_stride]: number of slices
 };
 
 typedef uint16_t bf16_t;  // raw bit pattern
@@ -72,11 +88,23 @@ __device__ __forceinline__ uint32_t div_g(const Params& p, uint32_t r) {
   return p.G == 1 ? r : __umulhi(r, p.g_magic);
 }
 
-__device__ __forceinline__ int32_t list_len(const Params& p, int g) {
-  return p.sel ? p.sel_count[g] : (int32_t)p.n;
+// Page lists.  List id `lid`: g with one list per KV head, g * m + query page otherwise.
+__device__ __forceinline__ int32_t list_len(const Params& p, int lid) {
+  return p.sel ? p.sel_count[lid] : (int32_t)p.n;
 }
-__device__ __forceinline__ int32_t list_at(const Params& p, int g, int32_t j) {
-  return p.sel ? p.sel[(int64_t)g * p.sel_stride + j] : j;
+__device__ __forceinline__ int32_t list_at(const Params& p, int lid, int32_t j) {
+  return p.sel ? p.sel[(int64_t)lid * p.sel_stride + j] : j;
+}
+__device__ __forceinline__ int list_id(const Params& p, int g, int i) {
+  return p.qp ? g * p.m + i / p.P : g;
+}
+// Pages of KV head g that some row attends ("owned" by one dK/dV workgroup each): its list, or the
+// union of its per-query-page lists.
+__device__ __forceinline__ int32_t owned_len(const Params& p, int g) {
+  return p.qp ? p.un_count[g] : list_len(p, g);
+}
+__device__ __forceinline__ int32_t owned_at(const Params& p, int g, int32_t j) {
+  return p.qp ? p.un_list[(int64_t)g * p.un_stride + j] : list_at(p, g, j);
 }
 
 }  // namespace oomb

@@ -1,7 +1,7 @@
 // Images of the selected K / V pages for the bf16 MFMA attention kernels (paper
-// Sec. 4.2: every query tile of a chunk attends the same page list, so the pages are
-// gathered through the page table and re-laid out once per call instead of once per
-// query tile).  An image is one half page (64 tokens x 128 dims, 16 KiB) in exactly
+// Sec. 4.2: every query tile of a chunk attends the same page list -- or, with one list
+// per query page, lists drawn from one union -- so the pages are gathered through the
+// page table and re-laid out once per call instead of once per query tile).  An image is one half page (64 tokens x 128 dims, 16 KiB) in exactly
 // the byte order of the LDS tile that the kernels read, so that their staging is a
 // plain copy:
 //   natural:    token r, granule c (dims 8c .. 8c+7) at (r * 16 + (c ^ (r & 15))) * 16
@@ -37,8 +37,8 @@ __global__ __launch_bounds__(256) void kv_layout_kernel(Params p, int32_t max_le
   const int nat_bit = is_v ? IMG_V_NAT : IMG_K_NAT, tr_bit = is_v ? IMG_V_TR : IMG_K_TR;
   if (!(kinds & (nat_bit | tr_bit))) return;
   const int32_t j = ht >> 1;
-  if (j >= list_len(p, g)) return;
-  const int64_t l = list_at(p, g, j);
+  if (j >= owned_len(p, g)) return;
+  const int64_t l = owned_at(p, g, j);
   const bf16_t* src = (is_v ? (const bf16_t*)p.v_pool : (const bf16_t*)p.k_pool) +
                       (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride +
                       (int64_t)(ht & 1) * 64 * p.pool_tok_stride;

@@ -90,36 +90,38 @@ template <int N> __device__ __forceinline__ void wait_copies() {
 }
 
 // Page list entries held in registers, 64 per window, two windows deep: lane j of a
-// window holds the logical page id of list entry base + j and its physical page.
+// window holds the logical page id of list entry base + j and, in `ph`, its physical
+// page -- or, with one list per query page, the position of the page in the KV head's
+// union list (where its images sit).  `lid` is the list id.
 // The main loops read them with v_readlane, so no iteration waits for a chain of
 // dependent memory loads (selection list -> page table); the next window is
 // fetched while the current one is consumed.
 struct PageWindow {
   int32_t l_cur, p_cur, l_nxt, p_nxt;
   int32_t base;
-  static __device__ __forceinline__ void fetch(const Params& p, int g, int32_t len, int32_t b, int lane,
+  static __device__ __forceinline__ void fetch(const Params& p, int lid, int32_t len, int32_t b, int lane,
                                                int32_t& l, int32_t& ph) {
     const int32_t j = b + lane;
     l = 0;
     ph = 0;
     if (j < len) {
-      l = list_at(p, g, j);
-      ph = p.page_table[l];
+      l = list_at(p, lid, j);
+      ph = p.qp ? p.qp_slot[(int64_t)lid * p.sel_stride + j] : p.page_table[l];
     }
   }
-  __device__ __forceinline__ void init(const Params& p, int g, int32_t len, int lane) {
+  __device__ __forceinline__ void init(const Params& p, int lid, int32_t len, int lane) {
     base = 0;
-    fetch(p, g, len, 0, lane, l_cur, p_cur);
-    fetch(p, g, len, 64, lane, l_nxt, p_nxt);
+    fetch(p, lid, len, 0, lane, l_cur, p_cur);
+    fetch(p, lid, len, 64, lane, l_nxt, p_nxt);
   }
   // j (wave-uniform, non-decreasing across calls) must satisfy base <= j; entries up to
   // j + 63 stay readable afterwards
-  __device__ __forceinline__ void advance(const Params& p, int g, int32_t len, int32_t j, int lane) {
+  __device__ __forceinline__ void advance(const Params& p, int lid, int32_t len, int32_t j, int lane) {
     if (j >= base + 64) {
       l_cur = l_nxt;
       p_cur = p_nxt;
       base += 64;
-      fetch(p, g, len, base + 64, lane, l_nxt, p_nxt);
+      fetch(p, lid, len, base + 64, lane, l_nxt, p_nxt);
     }
   }
   __device__ __forceinline__ int32_t page(int32_t j) const {
@@ -134,19 +136,56 @@ struct PageWindow {
   }
 };
 
-// Number of leading list entries of KV head g whose logical page is <= l_max (the
+// Number of leading entries of list `lid` whose logical page is <= l_max (the
 // list is ascending, so the invisible entries form a suffix).  64 entries per step,
 // one memory latency each.
-__device__ __forceinline__ int32_t visible_len(const Params& p, int g, int64_t l_max, int lane) {
-  int32_t len = list_len(p, g);
+__device__ __forceinline__ int32_t visible_len(const Params& p, int lid, int64_t l_max, int lane) {
+  int32_t len = list_len(p, lid);
   while (len > 0) {
     const int32_t j = len - 1 - lane;
-    const bool over = j >= 0 && (int64_t)list_at(p, g, j) > l_max;
+    const bool over = j >= 0 && (int64_t)list_at(p, lid, j) > l_max;
     const int n_over = __builtin_popcountll(__ballot(over));
     len -= n_over;
     if (n_over < 64) break;
   }
   return len;
+}
+
+// Row tiles of the forward and dQ kernels.  Row space of a KV head: block b = tb * G + hd holds the
+// 32 consecutive chunk tokens 32 tb .. 32 tb + 31 of query head g G + hd.  A tile is up to 8
+// consecutive blocks, one per wave.  With one list per KV head the tiles simply partition the
+// blocks; with one list per query page no tile may straddle two query pages, so every query page
+// (4 G blocks) gets ceil(4 G / 8) tiles of its own and the waves beyond its last block idle along
+// (they compute a copy of that block and store nothing).
+struct RowTile {
+  int32_t b_first, b_last;  // blocks of the tile
+  uint32_t bw;              // this wave's block (clamped to b_last)
+  bool valid;               // this wave owns a block
+  int lid;                  // list the tile's rows use
+};
+__host__ __device__ __forceinline__ int32_t row_tiles_per_head(int32_t C, int32_t G, int32_t m, int qp) {
+  const int32_t nblk = (C / 32) * G;
+  if (!qp) return (nblk + 7) / 8;
+  return m * ((nblk / m + 7) / 8);
+}
+__device__ __forceinline__ RowTile row_tile(const Params& p, int g, int32_t tile, int wave) {
+  RowTile t;
+  const int32_t nblk = (p.C / 32) * p.G;
+  if (!p.qp) {
+    t.b_first = tile * 8;
+    t.b_last = t.b_first + 7 < nblk ? t.b_first + 7 : nblk - 1;
+    t.lid = g;
+  } else {
+    const int32_t bpq = nblk / p.m, tpq = (bpq + 7) / 8;
+    const int32_t tau = tile / tpq, sub = tile - tau * tpq;
+    t.b_first = tau * bpq + sub * 8;
+    t.b_last = t.b_first + 7 < (tau + 1) * bpq ? t.b_first + 7 : (tau + 1) * bpq - 1;
+    t.lid = g * p.m + tau;
+  }
+  const int32_t b = t.b_first + wave;
+  t.valid = b <= t.b_last;
+  t.bw = (uint32_t)(t.valid ? b : t.b_last);
+  return t;
 }
 
 // max / sum across the two 32-lane halves of a wave (lanes l and l ^ 32).

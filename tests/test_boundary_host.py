@@ -124,3 +124,27 @@ def test_calibrate_rejects_bad_arguments_before_launch():
     assert l.oomb_calibrate(0, fake, 1 << 20, None, None) == api.ERR_INVALID_ARG
     assert l.oomb_calibrate(1, ctypes.c_void_p(0x1004), 1 << 20, ctypes.byref(out), None) == api.ERR_INVALID_ARG
     assert l.oomb_calibrate(1, fake, 16, ctypes.byref(out), None) == api.ERR_INVALID_ARG
+
+
+def test_per_query_page_entry_points_validate_before_launch():
+    d = _good_desc()
+    l = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    m = 4096 // 128
+    need_f = api.workspace_bytes(d, 64, api.OP_ATTN_FWD_QP)
+    need_b = api.workspace_bytes(d, 64, api.OP_ATTN_BWD_QP)
+    # worst case: the m lists of a KV head share no page -> images of m * (64 + m) pages per head
+    assert need_f >= 4 * m * (64 + m) * 2 * 32768
+    assert need_b > need_f
+    assert api.workspace_bytes(d, -1, api.OP_ATTN_FWD_QP) == 0
+    # lists are mandatory, with counts and a row stride that holds the local pages
+    assert l.oomb_paged_attn_fwd_qp(ctypes.byref(d), fake, fake, fake, fake, None, None, 96, fake, fake, fake,
+                                    need_f, None) == api.ERR_INVALID_ARG
+    assert l.oomb_paged_attn_fwd_qp(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 8, fake, fake, fake,
+                                    need_f, None) == api.ERR_INVALID_ARG
+    assert l.oomb_paged_attn_fwd_qp(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 64 + m, fake, fake, fake,
+                                    need_f - 1, None) == api.ERR_WORKSPACE
+    assert l.oomb_paged_attn_bwd_qp(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 64 + m, fake, fake, fake,
+                                    fake, fake, fake, None, 0, None) == api.ERR_WORKSPACE
+    assert l.oomb_paged_attn_bwd_qp(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 64 + m, fake, fake, None,
+                                    fake, fake, fake, fake, need_b, None) == api.ERR_INVALID_ARG
