@@ -133,8 +133,9 @@ def test_per_query_page_entry_points_validate_before_launch():
     m = 4096 // 128
     need_f = api.workspace_bytes(d, 64, api.OP_ATTN_FWD_QP)
     need_b = api.workspace_bytes(d, 64, api.OP_ATTN_BWD_QP)
-    # worst case: the m lists of a KV head share no page -> images of m * (64 + m) pages per head
-    assert need_f >= 4 * m * (64 + m) * 2 * 32768
+    # worst case: the m lists of a KV head share no page -> images of min(n, m * (64 + m)) pages per head
+    n = 65536 // 128
+    assert need_f >= 4 * min(n, m * (64 + m)) * 2 * 32768
     assert need_b > need_f
     assert api.workspace_bytes(d, -1, api.OP_ATTN_FWD_QP) == 0
     # lists are mandatory, with counts and a row stride that holds the local pages
