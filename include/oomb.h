@@ -154,6 +154,29 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Retrieval by voting (Sec. 4.2, the scoring equation): per KV head g and query page tau,
+ *   z[h][i][l]      = sm_scale * <Q[i,h], kbar[l][g]>          past pages l < n_past
+ *   p[h][i][.]      = softmax of z[h][i][.] over the past pages l
+ *   vote[g][tau][l] = sum of p[h][i][l] over the G heads h of group g and the P tokens i of query page tau
+ * and the k_eff = min(top_k, n_past) past pages with the largest vote are kept (ties to the
+ * lower logical id), followed by the local pages n_past .. n_past + tau that the rows of the
+ * query page can see; lists ascending.  kbar is the page mean as kept by oomb_kv_append /
+ * oomb_page_means; for bf16 tensors it is rounded to bf16 (nearest even) before the products,
+ * which run on bf16 matrix instructions with fp32 accumulation; softmax and vote sums are fp32,
+ * in a fixed order (results are bit-reproducible, but not bit-equal to another summation order).
+ *   q          [C][Hq][D]                         in
+ *   kbar_cache [>= n_past][Hkv][D] float          in
+ *   sel_pages  [Hkv][m][top_k + m] int32          out (unused tail = -1)
+ *   sel_count  [Hkv][m] int32                     out
+ *   votes_out  [Hkv][m][n_past] float or NULL     out
+ * Workspace: oomb_workspace_bytes(desc, top_k, OOMB_OP_VOTE_TOPK).  Returns
+ * OOMB_ERR_UNSUPPORTED when n_past exceeds 1,048,576 or Hkv * m exceeds 65,535.
+ */
+oomb_status oomb_page_vote_topk(const oomb_attn_desc* desc, const void* q, const float* kbar_cache, int32_t top_k,
+                                int32_t* sel_pages, int32_t* sel_count, float* votes_out, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
+
+/*
  * Attention with one page list per (KV head, query page) (Sec. 4.2: the votes are
  * aggregated for each of the m query pages of the chunk, so every query page
  * retrieves its own top-K key pages).  Same operators as oomb_paged_attn_fwd / _bwd,

@@ -20,7 +20,7 @@ EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd"
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
            "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
            "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
-           "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp"]
+           "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib():
         l.oomb_paged_attn_fwd_qp.argtypes = l.oomb_paged_attn_fwd.argtypes
         l.oomb_paged_attn_bwd_qp.restype = i32
         l.oomb_paged_attn_bwd_qp.argtypes = l.oomb_paged_attn_bwd.argtypes
+        l.oomb_page_vote_topk.restype = i32
+        l.oomb_page_vote_topk.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
@@ -189,6 +191,22 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
     if st != OK:
         raise OombError(st, "oomb_paged_attn_bwd")
     return d_q
+
+
+def page_vote_topk(desc: AttnDesc, q, kbar_cache, top_k: int, sel_pages=None, sel_count=None, votes_out=None,
+                   workspace=None):
+    """oomb_page_vote_topk.  Returns (sel_pages [Hkv][m][top_k + m] int32, sel_count [Hkv][m] int32)."""
+    m = desc.chunk_len // desc.page_size
+    if sel_pages is None:
+        sel_pages = torch.empty((desc.n_kv_heads, m, top_k + m), dtype=torch.int32, device=q.device)
+    if sel_count is None:
+        sel_count = torch.empty((desc.n_kv_heads, m), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(desc, top_k, OP_VOTE_TOPK, q.device, workspace)
+    st = lib().oomb_page_vote_topk(ctypes.byref(desc), _p(q), _p(kbar_cache), top_k, _p(sel_pages), _p(sel_count),
+                                   _p(votes_out), _p(workspace), nbytes, _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_page_vote_topk")
+    return sel_pages, sel_count
 
 
 def _qp_lists(desc, sel_pages, sel_count):

@@ -21,6 +21,9 @@ hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
 size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
+size_t vote_workspace_bytes(const Params& p, bool is_bf16, bool force_generic);
+hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const float* kbar, int32_t top_k, int32_t* sel,
+                            int32_t* sel_count, float* votes_out, void* ws, hipStream_t st);
 size_t qp_maps_bytes(const Params& p, int32_t stride);
 int32_t qp_union_cap(const Params& p, int32_t stride);
 hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st);
@@ -133,6 +136,9 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
       const size_t mfma = mfma_supported(p, desc->dtype == OOMB_BF16) ? bwd_mfma_workspace_bytes(p, (int32_t)max_len) : 0;
       return generic > mfma ? generic : mfma;
     }
+    case OOMB_OP_VOTE_TOPK:
+      if (top_k < 0) return 0;
+      return vote_workspace_bytes(p, desc->dtype == OOMB_BF16, force_generic());
     case OOMB_OP_ATTN_FWD_QP:
     case OOMB_OP_ATTN_BWD_QP: {
       if (top_k < 0) return 0;
@@ -282,6 +288,24 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
     if (e != hipSuccess) return OOMB_ERR_LAUNCH;
     e = launch_bwd_generic(p, bf, max_len, st);
   }
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_page_vote_topk(const oomb_attn_desc* desc, const void* q, const float* kbar_cache, int32_t top_k,
+                                int32_t* sel_pages, int32_t* sel_count, float* votes_out, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !kbar_cache || !sel_pages || !sel_count || top_k < 0) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(kbar_cache)) return OOMB_ERR_INVALID_ARG;
+  if (p.n_past > (1 << 20) || (int64_t)p.Hkv * p.m > 65535) return OOMB_ERR_UNSUPPORTED;
+  const bool bf = desc->dtype == OOMB_BF16;
+  if (!workspace || workspace_bytes < vote_workspace_bytes(p, bf, force_generic()) || !aligned16(workspace))
+    return OOMB_ERR_WORKSPACE;
+  p.q = q;
+  hipError_t e = launch_vote_topk(p, bf, force_generic(), kbar_cache, top_k, sel_pages, sel_count, votes_out, workspace,
+                                  (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

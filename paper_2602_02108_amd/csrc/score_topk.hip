@@ -153,16 +153,18 @@ __device__ __forceinline__ unsigned long long block_sum64(unsigned long long v, 
   return tot;
 }
 
-// Step S4.  One workgroup per KV head.  The k-th largest key is found by
-// bisection over its 32 bits (count of keys >= candidate), then the list is
+// Step S4.  One workgroup per list: per KV head, or (per_qp) per KV head and query page tau =
+// blockIdx.x % m, whose list ends with the tau + 1 local pages its rows can see.  The k-th largest
+// key is found by bisection over its 32 bits (count of keys >= candidate), then the list is
 // emitted in ascending logical id: all keys above the threshold, the lowest-id
 // keys equal to it, and the local pages.
 __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
     const float* __restrict__ scores, int64_t n_past, int32_t m, int32_t top_k,
-    int32_t* __restrict__ sel, int32_t* __restrict__ sel_count, int32_t lds_cap) {
+    int32_t* __restrict__ sel, int32_t* __restrict__ sel_count, int32_t lds_cap, int32_t per_qp) {
   extern __shared__ uint32_t keys[];  // first min(n_past, lds_cap) keys cached
   __shared__ unsigned long long red[SELECT_THREADS / 64];
   const int g = blockIdx.x, tid = threadIdx.x;
+  const int32_t n_loc = per_qp ? (int32_t)(blockIdx.x % m) + 1 : m;
   const float* sc = scores + (int64_t)g * n_past;
   const int32_t stride = top_k + m;
   int32_t* out = sel + (int64_t)g * stride;
@@ -236,12 +238,30 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
       }
     }
   }
-  for (int32_t j = tid; j < m; j += SELECT_THREADS) out[k_eff + j] = (int32_t)(n_past + j);
-  for (int32_t j = k_eff + m + tid; j < stride; j += SELECT_THREADS) out[j] = -1;
-  if (tid == 0) sel_count[g] = k_eff + m;
+  for (int32_t j = tid; j < n_loc; j += SELECT_THREADS) out[k_eff + j] = (int32_t)(n_past + j);
+  for (int32_t j = k_eff + n_loc + tid; j < stride; j += SELECT_THREADS) out[j] = -1;
+  if (tid == 0) sel_count[g] = k_eff + n_loc;
 }
 
 hipError_t launch_page_score_cached(const Params& p, const float* qbar, const float* cache, float* scores, hipStream_t st);
+
+static hipError_t launch_topk_select(const Params& p, const float* scores, int32_t top_k, int32_t* sel, int32_t* sel_count,
+                                     int per_qp, hipStream_t st) {
+  static int lds_cap_bytes = 0;
+  constexpr int WANT = 144 * 1024;
+  if (!lds_cap_bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, WANT);
+    lds_cap_bytes = (e == hipSuccess) ? WANT : 48 * 1024;
+    (void)hipGetLastError();
+  }
+  const int64_t cap = lds_cap_bytes / 4;
+  const int64_t cached = p.n_past < cap ? p.n_past : cap;
+  ProfScope prof_("topk_select", st);
+  topk_select_kernel<<<dim3((unsigned)(per_qp ? p.Hkv * p.m : p.Hkv)), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
+      scores, p.n_past, p.m, top_k, sel, sel_count, (int32_t)cap, per_qp);
+  return hipGetLastError();
+}
 
 // kbar_cache != nullptr: the page means come from the cache instead of the keys
 template <typename T, int D>
@@ -286,22 +306,13 @@ hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32
     if (p.D == 128) launch_scoring<float, 128>(p, A, qbar, scores, kbar_cache, st);
     else launch_scoring<float, 64>(p, A, qbar, scores, kbar_cache, st);
   }
-  static int lds_cap_bytes = 0;
-  constexpr int WANT = 144 * 1024;
-  if (!lds_cap_bytes) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, WANT);
-    lds_cap_bytes = (e == hipSuccess) ? WANT : 48 * 1024;
-    (void)hipGetLastError();
-  }
-  const int64_t cap = lds_cap_bytes / 4;
-  const int64_t cached = p.n_past < cap ? p.n_past : cap;
-  {
-    ProfScope prof_("topk_select", st);
-    topk_select_kernel<<<dim3(p.Hkv), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
-        scores, p.n_past, p.m, top_k, sel, sel_count, (int32_t)cap);
-  }
-  return hipGetLastError();
+  return launch_topk_select(p, scores, top_k, sel, sel_count, 0, st);
+}
+
+// votes [Hkv][m][n_past] -> one list per (KV head, query page), sel [Hkv][m][top_k + m]
+hipError_t launch_topk_select_qp(const Params& p, const float* votes, int32_t top_k, int32_t* sel, int32_t* sel_count,
+                                 hipStream_t st) {
+  return launch_topk_select(p, votes, top_k, sel, sel_count, 1, st);
 }
 
 }  // namespace oomb

@@ -1,0 +1,139 @@
+"""GPU parity of the retrieval by voting (paper Sec. 4.2, the scoring equation: softmax over the key
+pages per query token, summed per query page, top-K per query page) against the CPU oracle, and of
+the whole per-query-page path (votes -> lists -> attention forward / backward).
+
+The votes are floating point (fp32 on the GPU, double in the oracle) and decide integers (the
+lists).  Both sides take the page means in the same precision (bf16 for bf16 tensors); the votes are
+compared with a tolerance, and a list is accepted if it is the oracle's list or differs from it
+only in pages whose oracle votes tie with the k-th largest vote within that tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_02108_amd import api
+from paper_2602_02108_amd.workloads import WORKLOADS, Workload, make_inputs, torch_dtype
+
+import oracle as orc
+import parity_util as pu
+from test_gpu_qp_attention import gpu_fwd_bwd_qp
+
+pytestmark = pytest.mark.gpu
+
+VOTE_RTOL = 2e-4   # fp32 sums of up to G * P terms and exp2 / log2 of the hardware against double arithmetic
+
+
+def gpu_means(w, x):
+    desc = api.make_desc(x["q"], x["k_pool"], w.N, w.sm_scale, torch_dtype(w.grad_dtype))
+    cache = torch.zeros((w.n, w.Hkv, w.D), dtype=torch.float32, device="cuda")
+    api.page_means(desc, x["k_pool"], x["page_table"], 0, w.n, cache)
+    return desc, cache
+
+
+def gpu_vote(w, x, top_k):
+    desc, cache = gpu_means(w, x)
+    votes = torch.zeros((w.Hkv, w.m, max(w.n_past, 1)), dtype=torch.float32, device="cuda")
+    sel, cnt = api.page_vote_topk(desc, x["q"], cache, top_k, votes_out=votes)
+    torch.cuda.synchronize()
+    return sel.cpu().numpy(), cnt.cpu().numpy(), votes[:, :, : w.n_past].cpu().numpy(), cache.cpu().numpy()
+
+
+def check_lists(w, top_k, sel, cnt, osel, ocnt, ovotes, rtol=VOTE_RTOL):
+    """Every list: right length, ascending, the visible local pages at its end, and its past pages are
+    a valid top-k of the oracle's votes up to ties within rtol.  Returns the number of lists that are
+    not identical to the oracle's."""
+    k_eff = min(top_k, w.n_past)
+    differ = 0
+    assert sel.shape == (w.Hkv, w.m, top_k + w.m)
+    for g in range(w.Hkv):
+        for tau in range(w.m):
+            c = int(cnt[g, tau])
+            assert c == k_eff + tau + 1 == int(ocnt[g, tau])
+            lst = sel[g, tau, :c]
+            assert (np.diff(lst) > 0).all() and (sel[g, tau, c:] == -1).all()
+            assert list(lst[k_eff:]) == list(range(w.n_past, w.n_past + tau + 1))
+            if np.array_equal(sel[g, tau], osel[g, tau]):
+                continue
+            differ += 1
+            past = lst[:k_eff]
+            v = ovotes[g, tau]
+            vk = np.sort(v)[::-1][k_eff - 1]
+            dropped = np.setdiff1d(np.arange(w.n_past), past)
+            assert v[past].min() >= vk * (1 - rtol), (g, tau, v[past].min(), vk)
+            assert v[dropped].max() <= vk * (1 + rtol), (g, tau, v[dropped].max(), vk)
+    return differ
+
+
+def vote_parity(w: Workload, top_k: int):
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    sel, cnt, votes, cache = gpu_vote(w, x, top_k)
+    sh = pu.shape_of(w)
+    okb = orc.page_means(sh, hx["k_pool"], hx["page_table"], 0, w.n, np.zeros((w.n, w.Hkv, w.D), np.float32))
+    assert np.array_equal(cache.view(np.uint32), okb.view(np.uint32)), "page means differ"
+    osel, ocnt, ovotes = orc.page_vote_topk(sh, hx["q"], okb, top_k)
+    if w.n_past > 0:
+        err = np.abs(votes - ovotes) / np.maximum(ovotes, 1e-30)
+        rel = np.linalg.norm(votes - ovotes) / np.linalg.norm(ovotes)
+        print(w.name, f"votes: max rel {err.max():.2e}, rel-L2 {rel:.2e}", flush=True)
+        assert err.max() < VOTE_RTOL and rel < 2e-5
+        assert np.allclose(votes.sum(axis=2), w.P * w.G, rtol=1e-4)
+    differ = check_lists(w, top_k, sel, cnt, osel, ocnt, ovotes)
+    return x, hx, sel, cnt, osel, ocnt, differ
+
+
+VOTE_CASES = [
+    # matrix-core path: G = 7 (half-empty last row tile per query page), ragged last half tile of pages
+    (Workload("vote_g7", 14, 2, 128, 128, 128 * 3, 128 * (3 + 91), None, "bf16", "f32", 0.0884, extra_phys=2,
+              boost_frac=0.1, seed=41), 6),
+    (Workload("vote_g2", 4, 2, 128, 128, 128 * 5, 128 * (5 + 200), None, "bf16", "bf16", 0.0884, boost_frac=0.05,
+              seed=42), 16),
+    # plain kernels: fp32 tensors (means not rounded), and bf16 with a page size without a matrix kernel
+    (Workload("vote_f32", 4, 2, 64, 16, 16 * 5, 16 * (5 + 37), None, "f32", "f32", 0.125, boost_frac=0.1, seed=43), 4),
+    (Workload("vote_bf16_p64", 8, 2, 128, 64, 64 * 3, 64 * (3 + 50), None, "bf16", "f32", 0.088, boost_frac=0.1,
+              seed=44), 5),
+]
+
+
+@pytest.mark.parametrize("w,top_k", VOTE_CASES, ids=lambda v: v.name if isinstance(v, Workload) else str(v))
+def test_votes_and_lists(w, top_k):
+    *_, differ = vote_parity(w, top_k)
+    assert differ == 0, f"{differ} lists differ from the oracle's by near-ties"
+
+
+@pytest.mark.parametrize("top_k", [0, 1000])
+def test_top_k_zero_and_larger_than_the_history(top_k):
+    w = VOTE_CASES[0][0]
+    *_, sel, cnt, osel, ocnt, differ = vote_parity(w, top_k)
+    assert differ == 0
+
+
+def test_no_history():
+    w = VOTE_CASES[1][0].with_(name="vote_nohist", N=128 * 5, boost_frac=0.0)
+    x, hx, sel, cnt, osel, ocnt, differ = vote_parity(w, 4)
+    assert differ == 0 and (cnt == np.arange(1, w.m + 1)[None, :]).all()
+
+
+@pytest.mark.parametrize("case", [0, 1])
+def test_whole_path_votes_lists_attention(case):
+    """Votes -> lists on the GPU, forward and backward over those lists, against the oracle's own
+    lists and attention (the lists agree exactly on these seeded inputs)."""
+    w, top_k = VOTE_CASES[case]
+    x, hx, sel, cnt, osel, ocnt, differ = vote_parity(w, top_k)
+    assert differ == 0
+    res = gpu_fwd_bwd_qp(w, x, sel, cnt)
+    ref = orc.attn_fwd_bwd(pu.shape_of(w), hx["q"], hx["k_pool"], hx["v_pool"], hx["page_table"], hx["d_o"], osel, ocnt,
+                           prec="f32")
+    gd = w.dtype if w.grad_dtype == "f32" else "bf16"
+    pu.check("O", pu.f32(res["o"]), ref["o"], w.dtype)
+    pu.check("LSE", pu.f32(res["lse"]), ref["lse"], "bf16")
+    pu.check("dQ", pu.f32(res["dq"]), ref["dq"], w.dtype)
+    pu.check("dK pool", pu.f32(res["dk_pool"]), ref["dk_pool"], gd)
+    pu.check("dV pool", pu.f32(res["dv_pool"]), ref["dv_pool"], gd)
+
+
+def test_votes_are_deterministic():
+    w, top_k = VOTE_CASES[0]
+    x = make_inputs(w, "cuda")
+    a = gpu_vote(w, x, top_k)
+    b = gpu_vote(w, x, top_k)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
