@@ -89,6 +89,10 @@ def main():
     ap.add_argument("--cached-means", action="store_true",
                     help="score the pages from cached page means (kept by the paged manager at append time) "
                          "instead of streaming every past key; the default is the streaming scorer")
+    ap.add_argument("--retrieval", choices=["pooled", "votes"], default="pooled",
+                    help="pooled: one score per key page from the mean-pooled chunk query, one page list per KV head "
+                         "(the benchmark configuration); votes: per-token softmax votes summed per query page, one "
+                         "list per query page (the paper's scoring equation)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -113,6 +117,8 @@ def main():
         return N, api.make_desc(x["q"], x["k_pool"], N, w.sm_scale, gdt)
 
     top_k = w.top_k
+    votes = args.retrieval == "votes"
+    assert not votes or top_k is not None, "--retrieval votes needs a sparse workload"
     n_max, d_max = desc_at(grow - 1)
     ws_sc = torch.empty(max(api.workspace_bytes(d_max, top_k or 0, api.OP_SCORE_TOPK), 256), dtype=torch.uint8, device=dev)
     ws_fw = torch.empty(api.workspace_bytes(d_max, top_k if top_k is not None else -1, api.OP_ATTN_FWD), dtype=torch.uint8,
@@ -125,13 +131,37 @@ def main():
     lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
     dq = torch.empty_like(x["q"])
 
+    if votes:
+        ws_sc = torch.empty(api.workspace_bytes(d_max, top_k, api.OP_VOTE_TOPK), dtype=torch.uint8, device=dev)
+        ws_fw = torch.empty(api.workspace_bytes(d_max, top_k, api.OP_ATTN_FWD_QP), dtype=torch.uint8, device=dev)
+        ws_bw = torch.empty(api.workspace_bytes(d_max, top_k, api.OP_ATTN_BWD_QP), dtype=torch.uint8, device=dev)
+        sel = torch.empty((w.Hkv, w.m, top_k + w.m), dtype=torch.int32, device=dev)
+        cnt = torch.empty((w.Hkv, w.m), dtype=torch.int32, device=dev)
+
     kbar_cache = None
+    if votes and not args.cached_means:
+        kbar_stream = torch.zeros((n_max // w.P, w.Hkv, w.D), dtype=torch.float32, device=dev)
     if args.cached_means and top_k is not None:
         # the pool is pre-filled; its page means are what the manager would have cached append by append
         kbar_cache = torch.zeros((n_max // w.P, w.Hkv, w.D), dtype=torch.float32, device=dev)
         api.page_means(d_max, x["k_pool"], x["page_table"], 0, n_max // w.P, kbar_cache)
 
+    def step_votes(s):
+        N, desc = desc_at(s)
+        if kbar_cache is not None:
+            kb = kbar_cache
+        else:  # the page means are taken from the keys every chunk, as the method is written
+            kb = kbar_stream
+            api.page_means(desc, x["k_pool"], x["page_table"], 0, N // w.P - w.m, kb)
+        api.page_vote_topk(desc, x["q"], kb, top_k, sel, cnt, workspace=ws_sc)
+        api.paged_attn_fwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse, ws_fw)
+        api.paged_attn_bwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"],
+                              x["dk_pool"], x["dv_pool"], sel, cnt, dq, ws_bw)
+        return N
+
     def step(s):
+        if votes:
+            return step_votes(s)
         N, desc = desc_at(s)
         if top_k is not None:
             if kbar_cache is not None:
@@ -243,9 +273,12 @@ def main():
     # per phase: algorithmic FLOPs over the summed kernel times of the phase
     def phase_ms(names):
         return sum(kernels[k]["avg_ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
-    fwd_ms = phase_ms(["kv_layout", "attn_fwd_mfma"]) - 0.5 * phase_ms(["kv_layout"])  # kv_layout runs once per phase
-    bwd_ms = phase_ms(["bwd_prep", "bwd_layout", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + 0.5 * phase_ms(["kv_layout"])
-    sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "page_score_cached", "topk_select"])
+    # (kv_layout and qp_prepare run once per phase)
+    fwd_ms = phase_ms(["kv_layout", "qp_prepare", "attn_fwd_mfma"]) - 0.5 * phase_ms(["kv_layout", "qp_prepare"])
+    bwd_ms = phase_ms(["bwd_prep", "bwd_layout", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + \
+        0.5 * phase_ms(["kv_layout", "qp_prepare"])
+    sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "page_score_cached", "topk_select", "page_means",
+                       "kbar_image", "vote_lse", "vote_sum", "vote_finish"])
     phases = {"select_ms": sel_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
               "fwd_tflops": 4.0 * w.D * pairs_avg * w.Hq / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else None,
               "bwd_tflops": 10.0 * w.D * pairs_avg * w.Hq / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else None}
@@ -262,7 +295,9 @@ def main():
         "config": {"workload": w.name, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.D, "page_size": w.P,
                    "chunk": w.C, "history_tokens_first_step": w.N, "history_growth_per_step": w.C,
                    "top_k_pages": w.top_k, "local_pages": w.m, "grad_pool_dtype": w.grad_dtype,
-                   "scoring": "cached page means" if kbar_cache is not None else "streams every past key"},
+                   "scoring": "cached page means" if kbar_cache is not None else "streams every past key",
+                   "retrieval": "softmax votes, one list per query page" if votes else
+                                "pooled query score, one list per KV head"},
         "kv_gbps": kv_bytes / dt / 1e9,
         "frac_mfma_peak": flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "kernels": kernels,

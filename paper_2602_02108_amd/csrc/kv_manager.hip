@@ -8,6 +8,7 @@
 // The means and scores use the fixed fp32 operation order of the streaming scorer
 // (score_topk.hip), so both paths give the same bits.
 #include "common.h"
+#include "rowsum.h"
 
 #pragma clang fp contract(off)
 
@@ -46,6 +47,27 @@ __global__ __launch_bounds__(256) void page_means_kernel(Params p, int64_t first
   float acc = 0.0f;
   for (int t = 0; t < p.P; ++t) acc = __fadd_rn(acc, Elem<T>::load(base + (int64_t)t * p.pool_tok_stride));
   cache[((int64_t)l * p.Hkv + g) * p.D + d] = __fmul_rn(acc, inv_p);
+}
+
+// The same means for D = 64 / 128 with 16-byte loads: a group of LPR lanes walks one (page, KV head)
+// tile token by token (same addition order, same bits); this is the kernel that streams a whole
+// history when the means are not cached.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void page_means_vec_kernel(Params p, int64_t first, int64_t count, float inv_p,
+                                                             float* __restrict__ cache) {
+  constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PPB = 256 / LPR;
+  const int g = blockIdx.y;
+  const int lr = threadIdx.x % LPR;
+  const int64_t k = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+  if (k >= count) return;
+  const int64_t l = first + k;
+  const T* base = (const T*)p.k_pool + (int64_t)p.page_table[l] * p.pool_page_stride +
+                  (int64_t)g * p.pool_head_stride + lr * VEC;
+  float x[VEC];
+  seq_row_sum<T, 8>(base, p.pool_tok_stride, p.P, x);
+  float* out = cache + ((int64_t)l * p.Hkv + g) * D + lr * VEC;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) out[v] = __fmul_rn(x[v], inv_p);
 }
 
 // score[g][l] = tree sum over d of qbar[g][d] * cache[l][g][d] (stride-halving tree, strides D/2 .. 1):
@@ -112,6 +134,15 @@ hipError_t launch_page_means(const Params& p, bool is_bf16, int64_t first, int64
   const int64_t work = count * p.Hkv * p.D;
   const float inv_p = 1.0f / (float)p.P;
   ProfScope prof_("page_means", st);
+  if (p.D == 128 || p.D == 64) {
+    const int lpr = is_bf16 ? p.D / 8 : p.D / 4, ppb = 256 / lpr;
+    dim3 grid((unsigned)((count + ppb - 1) / ppb), (unsigned)p.Hkv);
+    if (is_bf16 && p.D == 128) page_means_vec_kernel<bf16_t, 128><<<grid, dim3(256), 0, st>>>(p, first, count, inv_p, cache);
+    else if (is_bf16) page_means_vec_kernel<bf16_t, 64><<<grid, dim3(256), 0, st>>>(p, first, count, inv_p, cache);
+    else if (p.D == 128) page_means_vec_kernel<float, 128><<<grid, dim3(256), 0, st>>>(p, first, count, inv_p, cache);
+    else page_means_vec_kernel<float, 64><<<grid, dim3(256), 0, st>>>(p, first, count, inv_p, cache);
+    return hipGetLastError();
+  }
   if (is_bf16) page_means_kernel<bf16_t><<<dim3((unsigned)((work + 255) / 256)), dim3(256), 0, st>>>(p, first, count, inv_p, cache);
   else page_means_kernel<float><<<dim3((unsigned)((work + 255) / 256)), dim3(256), 0, st>>>(p, first, count, inv_p, cache);
   return hipGetLastError();

@@ -7,57 +7,11 @@
 //   dot product as a stride-halving tree over d.  No fused multiply-add.
 // The page-mean kernel is HBM-bound: it streams every past key once.
 #include "common.h"
+#include "rowsum.h"
 
 #pragma clang fp contract(off)
 
 namespace oomb {
-
-template <typename T> struct Vec16;  // one 16-byte load worth of elements
-template <> struct Vec16<float> {
-  static constexpr int N = 4;
-  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
-    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
-  }
-};
-template <> struct Vec16<bf16_t> {
-  static constexpr int N = 8;
-  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
-    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
-    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
-    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
-    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
-  }
-};
-
-// Left-to-right sum of `count` rows (row stride `stride` elements) of the VEC
-// elements this lane owns.  Loads are issued U at a time, adds stay in order.
-template <typename T, int U>
-__device__ __forceinline__ void seq_row_sum(const T* base, int64_t stride, int count, float* acc) {
-  constexpr int VEC = Vec16<T>::N;
-#pragma unroll
-  for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
-  int t = 0;
-  for (; t + U <= count; t += U) {
-    uint4 r[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) r[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(t + u) * stride);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float f[VEC];
-      Vec16<T>::unpack(r[u], f);
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] = __fadd_rn(acc[v], f[v]);
-    }
-  }
-  for (; t < count; ++t) {
-    uint4 r = *reinterpret_cast<const uint4*>(base + (int64_t)t * stride);
-    float f[VEC];
-    Vec16<T>::unpack(r, f);
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = __fadd_rn(acc[v], f[v]);
-  }
-}
 
 // Step S1a: A[h][tau][d] = sum over the P tokens of query page tau of Q.
 template <typename T, int D>

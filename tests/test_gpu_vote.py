@@ -137,3 +137,76 @@ def test_votes_are_deterministic():
     a = gpu_vote(w, x, top_k)
     b = gpu_vote(w, x, top_k)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
+
+
+def _oracle_lists_of_head(w, hx, okb, g0, top_k):
+    """The oracle's votes and lists of every query page of KV head g0.  vote[g0][tau] depends only on
+    the rows of (g0, tau) and on the means of head g0, so each query page is a one-page problem of its
+    own; they run side by side in threads (the C function releases the interpreter lock)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import Shape
+    q = hx["q"]
+    kb = np.ascontiguousarray(okb[: w.n_past, g0:g0 + 1])
+    sub = Shape(w.G, 1, w.D, w.P, w.P, (w.n_past + 1) * w.P, w.sm_scale)
+
+    def one(tau):
+        qs = np.ascontiguousarray(q[tau * w.P:(tau + 1) * w.P, g0 * w.G:(g0 + 1) * w.G])
+        s, c, v = orc.page_vote_topk(sub, qs, kb, top_k)
+        return s[0, 0, : c[0, 0] - 1], v[0, 0]
+
+    with ThreadPoolExecutor(max_workers=min(16, orc.num_threads())) as ex:
+        res = list(ex.map(one, range(w.m)))
+    sel = np.full((w.m, top_k + w.m), -1, np.int32)
+    cnt = np.zeros(w.m, np.int32)
+    votes = np.stack([r[1] for r in res])
+    for tau, (past, _) in enumerate(res):
+        lst = list(past) + list(range(w.n_past, w.n_past + tau + 1))
+        sel[tau, : len(lst)] = lst
+        cnt[tau] = len(lst)
+    return sel, cnt, votes
+
+
+def test_votes_path_full_size():
+    """1M-token history in the configuration bench.py --retrieval votes times: the votes and lists of
+    one KV head against the oracle in full, then sampled rows (O, LSE, dQ) and sampled pages (dK, dV)
+    of that head over the oracle's lists, and the identities that hold at any size."""
+    import test_gpu_parity_full as full
+    w = WORKLOADS["qwen_sparse_1m"]
+    top_k, g0 = w.top_k, 1
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    sel, cnt, votes, cache = gpu_vote(w, x, top_k)
+    sh = pu.shape_of(w)
+    okb = orc.page_means(sh, hx["k_pool"], hx["page_table"], 0, w.n_past, np.zeros((w.n, w.Hkv, w.D), np.float32))
+    assert np.array_equal(cache[: w.n_past].view(np.uint32), okb[: w.n_past].view(np.uint32)), "page means differ"
+    osel_g, ocnt_g, ovotes_g = _oracle_lists_of_head(w, hx, okb, g0, top_k)
+    err = np.abs(votes[g0] - ovotes_g) / np.maximum(ovotes_g, 1e-30)
+    print(f"votes of head {g0}: max rel {err.max():.2e}", flush=True)
+    assert err.max() < VOTE_RTOL
+    # lists of the other heads are never read by the oracle calls below (rows and pages of head g0 only)
+    osel = np.full((w.Hkv, w.m, top_k + w.m), -1, np.int32)
+    ocnt = np.zeros((w.Hkv, w.m), np.int32)
+    for g in range(w.Hkv):
+        for tau in range(w.m):
+            osel[g, tau, : tau + 1] = np.arange(w.n_past, w.n_past + tau + 1)
+            ocnt[g, tau] = tau + 1
+    osel[g0], ocnt[g0] = osel_g, ocnt_g
+    one = w.with_(Hkv=1, Hq=w.G)
+    differ = check_lists(one, top_k, sel[g0:g0 + 1], cnt[g0:g0 + 1], osel[g0:g0 + 1], ocnt[g0:g0 + 1], ovotes_g[None])
+    assert differ == 0, f"{differ} lists of head {g0} differ from the oracle's by near-ties"
+    union = np.unique(osel_g[osel_g >= 0])
+    print(f"head {g0}: {len(union)} distinct pages in {w.m} lists of {top_k} + local", flush=True)
+
+    res = gpu_fwd_bwd_qp(w, x, sel, cnt)
+    rows = full._sample_rows(w, 200, 3)
+    rows = rows[(rows[:, 0] // w.G) == g0]
+    assert len(rows) >= 24
+    full._check_rows(w, hx, res, osel, ocnt, rows)
+    held = np.bincount(osel_g[osel_g >= 0], minlength=w.n)          # lists that hold each page
+    pages = [int(union[0]), int(np.argmax(held[: w.n_past])), int(w.n_past), int(w.n_past + w.m // 2), int(w.n - 1)]
+    full._check_units(w, hx, res, osel, ocnt, g0, sorted(set(pages)))
+    full._check_identities(w, x, res)
+    # pages in no list of head g0 are untouched
+    untouched = np.setdiff1d(np.arange(w.n_phys), hx["page_table"][union])
+    idx = torch.as_tensor(untouched, device="cuda")
+    assert not res["dk_pool"][idx, g0].any() and not res["dv_pool"][idx, g0].any()
