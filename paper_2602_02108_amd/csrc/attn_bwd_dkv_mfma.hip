@@ -428,13 +428,16 @@ template <typename TG>
 __global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(Params p, const float* __restrict__ partial,
                                                              int32_t max_len, int32_t n_split) {
   const int g = blockIdx.z;
-  const int32_t j = blockIdx.y;
-  if (j >= owned_len(p, g)) return;
-  int64_t first_part = ((int64_t)g * max_len + j) * n_split;
-  if (p.qp) {  // only pages that were cut into several units have partial pages
+  int32_t j = blockIdx.y;
+  int64_t first_part;
+  if (p.qp) {  // only the pages that were cut into several units have partial pages: blockIdx.y walks their list
+    if (j >= p.multi_count[g]) return;
+    j = p.multi_list[(int64_t)g * p.max_multi + j];
     n_split = p.un_ns[(int64_t)g * p.un_stride + j];
-    if (n_split <= 1) return;
     first_part = p.un_pbase[(int64_t)g * p.un_stride + j];
+  } else {
+    if (j >= list_len(p, g)) return;
+    first_part = ((int64_t)g * max_len + j) * n_split;
   }
   const int which = blockIdx.x >> 4;                       // 0: dK, 1: dV
   const int e4 = ((blockIdx.x & 15) * 256 + threadIdx.x);  // float4 index inside the 128 x 128 page
@@ -498,7 +501,7 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_
   if (e != hipSuccess) return e;
   if (p.qp || n_split > 1) {
     ProfScope prof_("bwd_dkv_reduce", st);
-    dim3 grid(32, (unsigned)max_len, (unsigned)p.Hkv);
+    dim3 grid(32, (unsigned)(p.qp ? p.max_multi : max_len), (unsigned)p.Hkv);
     if (p.grad_is_bf16) bwd_dkv_reduce_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(p, partial, max_len, n_split);
     else bwd_dkv_reduce_kernel<float><<<grid, dim3(256), 0, st>>>(p, partial, max_len, n_split);
     e = hipGetLastError();

@@ -254,7 +254,9 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   auto iteration = [&](const int32_t t, const int st, const bool general) __attribute__((always_inline)) {
     pw.advance(p, lid, T, t >> 1, lane);
     if (t + 1 < T2) copy_stage(t + 1, st ^ 1);
-    if (!general) {
+    if (!r_valid) {
+      // a wave without a block of its own (last row tile of a query page) only moves data and keeps the barriers
+    } else if (!general) {
       half_tile(st, false, 0);
     } else {
       const int64_t kfirst = ht_first(t);

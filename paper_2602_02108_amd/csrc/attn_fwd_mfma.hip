@@ -247,7 +247,7 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   if (T2 > 2) copy_k(2, 2);
   copies_landed();
   __syncthreads();
-  if (T2 > 0) {
+  if (T2 > 0 && r_valid) {
     qk_plain(sA, 0);
     qk_plain(sB, 8192);
     const int rel0 = rel_of(ht_first(0));
@@ -270,12 +270,14 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
       relA = rel_of(ht_first(t) + 32);
       relB = t + 1 < T2 ? rel_of(ht_first(t + 1)) : -1;
     }
-    step(0, kc, vc, kc + 8192, vc, sB, pB, pA, sA, relA, general);
+    // (a wave without a block of its own -- last row tile of a query page -- only moves data and
+    // keeps the barriers, leaving the SIMD to its partner)
+    if (r_valid) step(0, kc, vc, kc + 8192, vc, sB, pB, pA, sA, relA, general);
     copies_landed();
     __syncthreads();
     if (t + 3 < T2) copy_k(t + 3, r);
     if (t + 2 < T2) copy_v(t + 2, (r + 2) % 3);
-    step(1, kc + 8192, vc, kw, vw, sA, pA, pB, sB, relB, general);
+    if (r_valid) step(1, kc + 8192, vc, kw, vw, sA, pA, pB, sB, relB, general);
   };
   {
     int32_t t = 0;

@@ -46,6 +46,9 @@ struct Params {
   const int32_t* unit_count; // [Hkv]
   const int32_t* un_pbase;   // [Hkv][un_stride]: first partial slot of a union entry cut into slices, else -1
   const int32_t* un_ns;      // [Hkv][un_stride]: number of slices
+  const int32_t* multi_list; // [Hkv][max_multi]: the union entries that are cut into slices
+  const int32_t* multi_count;// [Hkv]
+  int32_t max_multi;
 };
 
 typedef uint16_t bf16_t;  // raw bit pattern

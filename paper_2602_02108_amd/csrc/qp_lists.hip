@@ -17,8 +17,9 @@ constexpr int QP_THREADS = 1024;
 constexpr int QP_SLICE = 8;  // query pages per dK/dV work unit
 
 struct QpLayout {
-  int32_t un_cap, max_units, max_pslots;
+  int32_t un_cap, max_units, max_pslots, max_multi;
   size_t off_cnt, off_fill, off_slot, off_un, off_uncnt, off_invoff, off_invqp, off_units, off_ucnt, off_pbase, off_ns;
+  size_t off_multi, off_mcnt;
   size_t bytes;
 };
 
@@ -31,6 +32,7 @@ QpLayout qp_layout(const Params& p, int32_t stride) {
   L.max_units = (int32_t)(L.un_cap + entries / QP_SLICE + 1);
   // a page held by c > QP_SLICE lists is cut into ceil(c / QP_SLICE) < c / 4 units
   L.max_pslots = (int32_t)(entries / 4 + 1);
+  L.max_multi = (int32_t)(entries / (QP_SLICE + 1) + 1);  // such a page is held by more than QP_SLICE lists
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += up256(bytes); return at; };
   L.off_cnt = take((size_t)p.Hkv * p.n * 4);
@@ -44,6 +46,8 @@ QpLayout qp_layout(const Params& p, int32_t stride) {
   L.off_ucnt = take((size_t)p.Hkv * 4);
   L.off_pbase = take((size_t)p.Hkv * L.un_cap * 4);
   L.off_ns = take((size_t)p.Hkv * L.un_cap * 4);
+  L.off_multi = take((size_t)p.Hkv * L.max_multi * 4);
+  L.off_mcnt = take((size_t)p.Hkv * 4);
   L.bytes = o;
   return L;
 }
@@ -52,6 +56,7 @@ size_t qp_maps_bytes(const Params& p, int32_t stride) { return qp_layout(p, stri
 int32_t qp_union_cap(const Params& p, int32_t stride) { return qp_layout(p, stride).un_cap; }
 int32_t qp_max_units(const Params& p, int32_t stride) { return qp_layout(p, stride).max_units; }
 int32_t qp_max_pslots(const Params& p, int32_t stride) { return qp_layout(p, stride).max_pslots; }
+int32_t qp_max_multi(const Params& p, int32_t stride) { return qp_layout(p, stride).max_multi; }
 
 // exclusive prefix of v over the workgroup's threads (thread order) and the total; two barriers
 __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t* wave_tot, int32_t& total) {
@@ -81,6 +86,7 @@ __global__ __launch_bounds__(QP_THREADS) void qp_prepare_kernel(Params p, int32_
                                                                 int32_t* __restrict__ invoff_all, int32_t* __restrict__ invqp_all,
                                                                 int4* __restrict__ units_all, int32_t* __restrict__ ucnt,
                                                                 int32_t* __restrict__ pbase_all, int32_t* __restrict__ ns_all,
+                                                                int32_t* __restrict__ multi_all, int32_t* __restrict__ mcnt,
                                                                 int32_t max_pslots) {
   __shared__ int32_t wave_tot[QP_THREADS / 64];
   const int g = blockIdx.x, tid = threadIdx.x;
@@ -95,6 +101,7 @@ __global__ __launch_bounds__(QP_THREADS) void qp_prepare_kernel(Params p, int32_
   int4* units = units_all + (int64_t)g * p.max_units;
   int32_t* pbase = pbase_all + (int64_t)g * p.un_stride;
   int32_t* ns_out = ns_all + (int64_t)g * p.un_stride;
+  int32_t* multi = multi_all + (int64_t)g * p.max_multi;
   const int32_t* sel = p.sel + (int64_t)g * entries;
   const int32_t* sel_count = p.sel_count + (int64_t)g * m;
 
@@ -161,15 +168,17 @@ __global__ __launch_bounds__(QP_THREADS) void qp_prepare_kernel(Params p, int32_
   // 4. dK/dV work units: union entry u with c query pages -> ceil(c / QP_SLICE) units
   const int32_t per_u = (n_un + QP_THREADS - 1) / QP_THREADS;
   const int32_t u0 = tid * per_u < n_un ? tid * per_u : n_un, u1 = u0 + per_u < n_un ? u0 + per_u : n_un;
-  int32_t my_units = 0, my_slots = 0;
+  int32_t my_units = 0, my_slots = 0, my_multi = 0;
   for (int32_t u = u0; u < u1; ++u) {
     const int32_t ns = (invoff[u + 1] - invoff[u] + QP_SLICE - 1) / QP_SLICE;
     my_units += ns;
     my_slots += ns > 1 ? ns : 0;
+    my_multi += ns > 1;
   }
-  int32_t n_units, n_slots;
+  int32_t n_units, n_slots, n_multi;
   int32_t k_at = block_exclusive_scan(my_units, wave_tot, n_units);
   int32_t s_at = block_exclusive_scan(my_slots, wave_tot, n_slots);
+  int32_t m_at = block_exclusive_scan(my_multi, wave_tot, n_multi);
   for (int32_t u = u0; u < u1; ++u) {
     const int32_t c = invoff[u + 1] - invoff[u];
     const int32_t ns = (c + QP_SLICE - 1) / QP_SLICE;
@@ -181,9 +190,15 @@ __global__ __launch_bounds__(QP_THREADS) void qp_prepare_kernel(Params p, int32_
       units[k_at + s] = make_int4(u, q0, qc, ns > 1 ? base + s : -1);
     }
     k_at += ns;
-    if (ns > 1) s_at += ns;
+    if (ns > 1) {
+      s_at += ns;
+      multi[m_at++] = u;
+    }
   }
-  if (tid == 0) ucnt[g] = n_units;
+  if (tid == 0) {
+    ucnt[g] = n_units;
+    mcnt[g] = n_multi;
+  }
 }
 
 // Points the maps of `p` into the workspace block `ws` (qp_maps_bytes long) and enqueues the kernel
@@ -203,11 +218,15 @@ hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st) {
   p.unit_count = (const int32_t*)(b + L.off_ucnt);
   p.un_pbase = (const int32_t*)(b + L.off_pbase);
   p.un_ns = (const int32_t*)(b + L.off_ns);
+  p.multi_list = (const int32_t*)(b + L.off_multi);
+  p.multi_count = (const int32_t*)(b + L.off_mcnt);
+  p.max_multi = L.max_multi;
   ProfScope prof_("qp_prepare", st);
   qp_prepare_kernel<<<dim3((unsigned)p.Hkv), dim3(QP_THREADS), 0, st>>>(
       p, (int32_t*)(b + L.off_cnt), (int32_t*)(b + L.off_fill), (int32_t*)(b + L.off_slot), (int32_t*)(b + L.off_un),
       (int32_t*)(b + L.off_uncnt), (int32_t*)(b + L.off_invoff), (int32_t*)(b + L.off_invqp), (int4*)(b + L.off_units),
-      (int32_t*)(b + L.off_ucnt), (int32_t*)(b + L.off_pbase), (int32_t*)(b + L.off_ns), L.max_pslots);
+      (int32_t*)(b + L.off_ucnt), (int32_t*)(b + L.off_pbase), (int32_t*)(b + L.off_ns), (int32_t*)(b + L.off_multi),
+      (int32_t*)(b + L.off_mcnt), L.max_pslots);
   return hipGetLastError();
 }
 

@@ -113,6 +113,13 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
 
   auto iteration = [&](const int32_t t, const int buf) __attribute__((always_inline)) {
     if (t + 1 < n_ht) copy_ht(t + 1, buf ^ 1);
+    // (a wave without a block of its own only moves data and keeps the barriers; in pass 2 it votes 0)
+    if (!rt.valid) {
+      if (PASS == 2 && hh == 0) {
+        *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + lq) * 4)) = 0.f;
+        *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + 32 + lq) * 4)) = 0.f;
+      }
+    } else
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       f32x16 s;
