@@ -6,11 +6,12 @@
 //
 // The logits are a dense contraction, rows (C G per KV head) x pages (n_past) x D, so they
 // run on the matrix cores (bf16 operands: the page means are rounded to bf16 once), in two
-// passes over the same row tiles as the attention kernels:
+// passes over row tiles of 8 blocks of 32 rows (the row space of the attention kernels):
 //   pass 1  S^T = Kbar Q^T: a lane owns a query row; online max / sum -> log2-sum-exp per row
 //   pass 2  S = Q Kbar^T (operands swapped, same fragments): a lane owns a page column and
 //           16 rows; p = exp2(c S - lse2[row]) summed down the column, then over the 8 waves
-//           in a fixed order -> one partial vote per (row tile, page)
+//           in a fixed order -> one partial vote per (row tile, page); a tile whose rows belong
+//           to two query pages keeps two partial votes, one per query page
 // then the partial votes of a query page's row tiles are added (fixed order) and the top-K
 // selection kernel runs once per (KV head, query page).  No atomics: bit-reproducible.
 // Shapes without a matrix kernel (fp32 tensors, D or P != 128) take two plain kernels.
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void kbar_image_kernel(Params p, const float* 
 
 // ---- the two passes -----------------------------------------------------------------------------
 // PASS = 1: lse2_rs[g][row] = log2 sum over past pages of exp2(c * logit), row-space index.
-// PASS = 2: part[((g m + tau) tpq + sub) n_pad + page] = sum over the rows of the tile of
-//           exp2(c * logit - lse2[row]).
+// PASS = 2: part[((g tiles + tile) 2 + k) n_pad + page] = sum over the rows of the tile that belong to
+//           its first (k = 0) / second (k = 1) query page of exp2(c * logit - lse2[row]).
 template <int PASS>
 __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const unsigned char* __restrict__ kb_img,
                                                                int32_t n_ht, float* __restrict__ lse2_rs, int64_t rows_pad,
@@ -73,7 +74,11 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
   }
   if (tile >= tiles_per_head) return;
 
-  const RowTile rt = row_tile(p, g, tile, wave);  // (p.qp is set: tiles never straddle query pages)
+  const RowTile rt = row_tile(p, g, tile, wave);  // (p.qp is clear: the tiles partition the row space)
+  // query page of a block: b / bpq.  The waves from `split` on belong to the tile's second query page.
+  const int32_t bpq = (p.P / 32) * p.G;
+  const int32_t tau_lo = rt.b_first / bpq;
+  const int32_t split = rt.b_last / bpq != tau_lo ? (tau_lo + 1) * bpq - rt.b_first : 8;
   const uint32_t bw = rt.bw, tbw = div_g(p, bw);
   const int i = (int)(32 * tbw + lq), h = g * p.G + (int)(bw - tbw * p.G);
   const bf16_t* qrow = (const bf16_t*)p.q + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride;
@@ -104,8 +109,7 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
       lse_r[x] = rt.valid ? lse2_rs[(int64_t)g * rows_pad + (int64_t)32 * bw + row] : INFINITY;  // idle waves vote 0
     }
   }
-  const int32_t tpq = tiles_per_head / p.m, tau = tile / tpq, sub = tile - tau * tpq;
-  float* const part_t = PASS == 2 ? part + (((int64_t)g * p.m + tau) * tpq + sub) * n_pad : nullptr;
+  float* const part_t = PASS == 2 ? part + ((int64_t)g * tiles_per_head + tile) * 2 * n_pad : nullptr;
 
   if (n_ht > 0) copy_ht(0, 0);
   wait_copies<0>();
@@ -161,12 +165,19 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
     wait_copies<0>();
     __syncthreads();
     if (PASS == 2 && wave == (t & 7)) {
-      // votes of half tile t: the 8 waves' column sums, added in wave order
-      float v = 0.f;
+      // votes of half tile t: the waves' column sums, added in wave order, per query page of the tile
+      float v0 = 0.f, v1 = 0.f;
 #pragma unroll
-      for (int w = 0; w < 8; ++w) v += *reinterpret_cast<const float*>(smem + (VT_RED + ((buf * 8 + w) * 64 + lane) * 4));
+      for (int w = 0; w < 8; ++w) {
+        const float x = *reinterpret_cast<const float*>(smem + (VT_RED + ((buf * 8 + w) * 64 + lane) * 4));
+        if (w < split) v0 += x;
+        else v1 += x;
+      }
       const int64_t page = (int64_t)64 * t + lane;
-      if (page < p.n_past) part_t[page] = v;
+      if (page < p.n_past) {
+        part_t[page] = v0;
+        if (split < 8) part_t[n_pad + page] = v1;
+      }
     }
   };
   for (int32_t t = 0; t < n_ht; t += 2) {
@@ -181,15 +192,19 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
   }
 }
 
-// votes[g][tau][l] = sum over the row tiles of the query page (ascending) of their partial votes
+// votes[g][tau][l] = sum over the row tiles that hold rows of the query page (ascending) of their
+// partial votes for it
 __global__ __launch_bounds__(256) void vote_finish_kernel(const float* __restrict__ part, float* __restrict__ votes,
-                                                          int64_t n_past, int64_t n_pad, int32_t tpq) {
+                                                          int64_t n_past, int64_t n_pad, int32_t tiles, int32_t m, int32_t bpq) {
   const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t q = blockIdx.y;  // g * m + tau
+  const int32_t q = blockIdx.y, g = q / m, tau = q - g * m;
   if (l >= n_past) return;
   float v = 0.f;
-  for (int32_t s = 0; s < tpq; ++s) v += part[(q * tpq + s) * n_pad + l];
-  votes[q * n_past + l] = v;
+  for (int32_t t = tau * bpq / 8; t <= ((tau + 1) * bpq - 1) / 8; ++t) {
+    const int32_t k = (8 * t) / bpq == tau ? 0 : 1;  // the tile's first or second query page
+    v += part[(((int64_t)g * tiles + t) * 2 + k) * n_pad + l];
+  }
+  votes[(int64_t)q * n_past + l] = v;
 }
 
 // ---- shapes without a matrix kernel ---------------------------------------------------------------
@@ -259,13 +274,13 @@ static VoteLayout vote_layout(const Params& p, bool mfma) {
   const int64_t np1 = p.n_past > 0 ? p.n_past : 1;
   L.n_ht = (int32_t)((p.n_past + 63) / 64);
   L.n_pad = (int64_t)(L.n_ht > 0 ? L.n_ht : 1) * 64;
-  L.tpq = mfma ? row_tiles_per_head(p.C, p.G, p.m, 1) / p.m : 1;
+  L.tpq = mfma ? row_tiles_per_head(p.C, p.G, p.m, 0) : 1;  // row tiles per KV head
   L.rows_pad = ((int64_t)p.C * p.G + 255) / 256 * 256;
   size_t o = 0;
   auto take = [&](size_t b) { const size_t at = o; o += vt_up(b); return at; };
   L.off_img = take(mfma ? (size_t)p.Hkv * (L.n_ht > 0 ? L.n_ht : 1) * 16384 : 0);
   L.off_lse = take(mfma ? (size_t)p.Hkv * L.rows_pad * 4 : (size_t)p.Hq * p.C * 4);
-  L.off_part = take(mfma ? (size_t)p.Hkv * p.m * L.tpq * L.n_pad * 4 : 0);
+  L.off_part = take(mfma ? (size_t)p.Hkv * L.tpq * 2 * L.n_pad * 4 : 0);
   L.off_votes = take((size_t)p.Hkv * p.m * np1 * 4);
   L.bytes = o;
   return L;
@@ -281,7 +296,7 @@ hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const fl
   const VoteLayout L = vote_layout(p, mfma);
   unsigned char* b = (unsigned char*)ws;
   float* votes = votes_out ? votes_out : (float*)(b + L.off_votes);
-  p.qp = 1;
+  p.qp = 0;
   if (p.n_past > 0 && mfma) {
     static bool attr_set = false;
     if (!attr_set) {
@@ -298,7 +313,7 @@ hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const fl
       ProfScope prof_("kbar_image", st);
       kbar_image_kernel<<<dim3((unsigned)L.n_ht, (unsigned)p.Hkv), dim3(256), 0, st>>>(p, kbar, img, L.n_ht);
     }
-    const int tiles = row_tiles_per_head(p.C, p.G, p.m, 1);
+    const int tiles = L.tpq;
     const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
     const int per = xcd_map ? 8 / p.Hkv : 1;
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
@@ -315,7 +330,7 @@ hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const fl
     {
       ProfScope prof_("vote_finish", st);
       vote_finish_kernel<<<dim3((unsigned)((p.n_past + 255) / 256), (unsigned)(p.Hkv * p.m)), dim3(256), 0, st>>>(
-          part, votes, p.n_past, L.n_pad, L.tpq);
+          part, votes, p.n_past, L.n_pad, tiles, p.m, (p.P / 32) * p.G);
     }
   } else if (p.n_past > 0) {
     float* lse = (float*)(b + L.off_lse);
