@@ -330,3 +330,50 @@ def attn_fwd_bwd(sh: Shape, q, k_pool, v_pool, page_table, d_o, sel=None, sel_co
     attn_bwd_dkv(sh, q, k_pool, v_pool, page_table, lse, dl, d_o, dk_pool, dv_pool, sel, sel_count,
                  prec=prec)
     return dict(o=o, lse=lse, delta=dl, dq=dq, dk_pool=dk_pool, dv_pool=dv_pool)
+
+
+# ---------------------------------------------------------------------------------------------
+# Offloaded KV cache (Sec. 4.3: the KV cache and its gradients live in host memory; the pages a
+# chunk attends are brought to the device, the gradients of those pages are taken back).  Pure
+# data movement, written as plain loops over (KV head, list entry).
+
+def offload_plan(sh: Shape, sel, sel_count):
+    """Staging slots for the pages that some KV head's list holds: slots are numbered in ascending
+    logical page order over the union of the lists.  Returns (stage_table [n] int32, -1 for pages that
+    are not staged; slot_pages [n_slots] int32, the logical page of every slot)."""
+    sel = _i32(sel)
+    cnt = _i32(sel_count)
+    held = np.zeros(sh.n, dtype=bool)
+    for g in range(sh.Hkv):
+        held[sel[g, : cnt[g]]] = True
+    slot_pages = np.flatnonzero(held).astype(np.int32)
+    stage_table = np.full(sh.n, -1, dtype=np.int32)
+    stage_table[slot_pages] = np.arange(len(slot_pages), dtype=np.int32)
+    return stage_table, slot_pages
+
+
+def offload_fetch(sh: Shape, host_k, host_v, page_table, sel, sel_count, stage_table, stage_k, stage_v):
+    """stage[stage_table[l]][g] = host[page_table[l]][g] for every page l in the list of KV head g (K and V);
+    nothing else of the staging pools is written.  Works on copies, returns (stage_k, stage_v)."""
+    sel, cnt, pt = _i32(sel), _i32(sel_count), _i32(page_table)
+    stage_k, stage_v = stage_k.copy(), stage_v.copy()
+    for g in range(sh.Hkv):
+        for j in range(cnt[g]):
+            l = sel[g, j]
+            stage_k[stage_table[l], g] = host_k[pt[l], g]
+            stage_v[stage_table[l], g] = host_v[pt[l], g]
+    return stage_k, stage_v
+
+
+def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_table, sel, sel_count, stage_table):
+    """host[page_table[l]][g] += stage[stage_table[l]][g] for every page l in the list of KV head g (dK and
+    dV), in the arithmetic of the host pool's dtype (float32 here; callers with bf16 pools round the sum).
+    Works on copies, returns (host_dk, host_dv)."""
+    sel, cnt, pt = _i32(sel), _i32(sel_count), _i32(page_table)
+    host_dk, host_dv = host_dk.copy(), host_dv.copy()
+    for g in range(sh.Hkv):
+        for j in range(cnt[g]):
+            l = sel[g, j]
+            host_dk[pt[l], g] = host_dk[pt[l], g] + stage_dk[stage_table[l], g]
+            host_dv[pt[l], g] = host_dv[pt[l], g] + stage_dv[stage_table[l], g]
+    return host_dk, host_dv
