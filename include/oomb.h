@@ -243,6 +243,47 @@ oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_page
                                  int32_t* sel_count, void* hip_stream);
 
 /*
+ * Offloaded KV cache (Sec. 4.3: the KV cache and its gradients are kept in host memory, the
+ * pages a chunk needs are transferred asynchronously; pinned memory and dedicated streams).
+ * The host pools are PINNED HOST memory that the device can address (hipHostMalloc, or a
+ * pinned torch tensor); they have the layout and strides of the descriptor's pools.  The
+ * transfers are kernels that read / write that memory directly, one workgroup per (list
+ * entry, KV head) tile, enqueued on hip_stream like everything else: put them on a stream of
+ * their own to overlap them with computation, and order them against the attention calls
+ * with events.  The page lists are the per-KV-head lists of oomb_page_score_topk*.
+ *
+ * oomb_offload_plan: staging slots for the pages that some KV head's list holds, numbered in
+ *   ascending logical page order over the union of the lists.
+ *     stage_table [n] int32 device, out: slot of a staged logical page, -1 otherwise
+ *     slot_pages  [min(n, Hkv * sel_stride)] int32 device, out: logical page of every slot
+ *     n_slots     [1] int32 device, out
+ * oomb_offload_fetch: for every page l in the list of KV head g,
+ *     stage_k / stage_v [stage_table[l]][g][:][:] = host_k / host_v [page_table[l]][g][:][:]
+ *   bit for bit; if stage_dk / stage_dv are given (both or neither) the same tiles of the
+ *   gradient staging pools are zeroed.  Staging pools: device memory, descriptor strides, at
+ *   least min(n, Hkv * sel_stride) pages; tiles of a slot that belong to a KV head whose list
+ *   does not hold the page are left alone and are never read by the attention kernels.
+ *   The attention entry points then run on the staging pools with page_table = stage_table
+ *   (their descriptor keeps num_phys_pages >= n: the bound is on the table's domain).
+ * oomb_offload_writeback: for the same (l, g),
+ *     host_dk / host_dv [page_table[l]][g] += stage_dk / stage_dv [stage_table[l]][g]
+ *   in float (rounded to the pool's dtype for bf16 pools); nothing else is written.
+ * Errors: OOMB_ERR_INVALID_ARG also for a host pool that is not device-addressable memory
+ * (checked with hipPointerGetAttributes before anything is launched).
+ */
+oomb_status oomb_offload_plan(const oomb_attn_desc* desc, const int32_t* sel_pages, const int32_t* sel_count,
+                              int32_t sel_stride, int32_t* stage_table, int32_t* slot_pages, int32_t* n_slots,
+                              void* hip_stream);
+oomb_status oomb_offload_fetch(const oomb_attn_desc* desc, const void* host_k_pool, const void* host_v_pool,
+                               const int32_t* page_table, const int32_t* sel_pages, const int32_t* sel_count,
+                               int32_t sel_stride, const int32_t* stage_table, void* stage_k, void* stage_v,
+                               void* stage_dk, void* stage_dv, void* hip_stream);
+oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage_dk, const void* stage_dv,
+                                   void* host_dk_pool, void* host_dv_pool, const int32_t* page_table,
+                                   const int32_t* sel_pages, const int32_t* sel_count, int32_t sel_stride,
+                                   const int32_t* stage_table, void* hip_stream);
+
+/*
  * Benchmark aid (not part of the paper's method): per-kernel device time.  While
  * enabled (on = 1), every kernel the library launches is bracketed by two HIP events
  * recorded on the caller's stream (events are host objects created on demand; no

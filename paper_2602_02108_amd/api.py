@@ -20,7 +20,8 @@ EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd"
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
            "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
            "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
-           "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk"]
+           "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk",
+           "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -68,6 +69,12 @@ def lib():
         l.oomb_paged_attn_bwd_qp.argtypes = l.oomb_paged_attn_bwd.argtypes
         l.oomb_page_vote_topk.restype = i32
         l.oomb_page_vote_topk.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
+        l.oomb_offload_plan.restype = i32
+        l.oomb_offload_plan.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp]
+        l.oomb_offload_fetch.restype = i32
+        l.oomb_offload_fetch.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        l.oomb_offload_writeback.restype = i32
+        l.oomb_offload_writeback.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
@@ -207,6 +214,49 @@ def page_vote_topk(desc: AttnDesc, q, kbar_cache, top_k: int, sel_pages=None, se
     if st != OK:
         raise OombError(st, "oomb_page_vote_topk")
     return sel_pages, sel_count
+
+
+def _stream_of(stream, t):
+    return ctypes.c_void_p(stream.cuda_stream) if stream is not None else _stream(t)
+
+
+def offload_plan(desc: AttnDesc, sel_pages, sel_count, stage_table=None, slot_pages=None, n_slots=None, stream=None):
+    """oomb_offload_plan.  Returns (stage_table [n] int32, slot_pages [min(n, Hkv * stride)] int32, n_slots [1] int32),
+    all on the device of sel_pages."""
+    n = desc.ctx_len // desc.page_size
+    stride = int(sel_pages.stride(0))
+    dev = sel_pages.device
+    if stage_table is None:
+        stage_table = torch.empty(n, dtype=torch.int32, device=dev)
+    if slot_pages is None:
+        slot_pages = torch.empty(min(n, desc.n_kv_heads * stride), dtype=torch.int32, device=dev)
+    if n_slots is None:
+        n_slots = torch.empty(1, dtype=torch.int32, device=dev)
+    st = lib().oomb_offload_plan(ctypes.byref(desc), _p(sel_pages), _p(sel_count), stride, _p(stage_table), _p(slot_pages),
+                                 _p(n_slots), _stream_of(stream, sel_pages))
+    if st != OK:
+        raise OombError(st, "oomb_offload_plan")
+    return stage_table, slot_pages, n_slots
+
+
+def offload_fetch(desc: AttnDesc, host_k_pool, host_v_pool, page_table, sel_pages, sel_count, stage_table, stage_k, stage_v,
+                  stage_dk=None, stage_dv=None, stream=None) -> None:
+    """oomb_offload_fetch: host_*_pool are pinned host tensors (or device tensors) with the pools' layout."""
+    st = lib().oomb_offload_fetch(ctypes.byref(desc), _p(host_k_pool), _p(host_v_pool), _p(page_table), _p(sel_pages),
+                                  _p(sel_count), int(sel_pages.stride(0)), _p(stage_table), _p(stage_k), _p(stage_v),
+                                  _p(stage_dk), _p(stage_dv), _stream_of(stream, stage_k))
+    if st != OK:
+        raise OombError(st, "oomb_offload_fetch")
+
+
+def offload_writeback(desc: AttnDesc, stage_dk, stage_dv, host_dk_pool, host_dv_pool, page_table, sel_pages, sel_count,
+                      stage_table, stream=None) -> None:
+    """oomb_offload_writeback: host pools += the staged gradient tiles of the listed pages."""
+    st = lib().oomb_offload_writeback(ctypes.byref(desc), _p(stage_dk), _p(stage_dv), _p(host_dk_pool), _p(host_dv_pool),
+                                      _p(page_table), _p(sel_pages), _p(sel_count), int(sel_pages.stride(0)),
+                                      _p(stage_table), _stream_of(stream, stage_dk))
+    if st != OK:
+        raise OombError(st, "oomb_offload_writeback")
 
 
 def _qp_lists(desc, sel_pages, sel_count):

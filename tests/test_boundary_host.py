@@ -149,3 +149,22 @@ def test_per_query_page_entry_points_validate_before_launch():
                                     fake, fake, fake, None, 0, None) == api.ERR_WORKSPACE
     assert l.oomb_paged_attn_bwd_qp(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 64 + m, fake, fake, None,
                                     fake, fake, fake, fake, need_b, None) == api.ERR_INVALID_ARG
+
+
+def test_offload_entry_points_validate_before_launch():
+    d = _good_desc()
+    l = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    m = 4096 // 128
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 8, fake, fake, fake, None) == api.ERR_INVALID_ARG  # stride < m
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, None, 64 + m, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    # gradient staging pools come in pairs
+    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, 64 + m, fake, fake, fake, fake, None,
+                                None) == api.ERR_INVALID_ARG
+    # a host pool the device cannot address (here: not memory at all) is refused before any launch
+    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, 64 + m, fake, fake, fake, None, None,
+                                None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, 64 + m, fake,
+                                    None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, None, fake, fake, fake, fake, 64 + m, fake,
+                                    None) == api.ERR_INVALID_ARG
