@@ -60,6 +60,137 @@ def cpu_baseline(w, x, sample_tokens):
             "seconds": t2 - t0}
 
 
+def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max):
+    """Step = cached-means selection -> staging plan -> fetch of the selected pages from pinned host pools ->
+    forward + backward on the staging pools -> write-back of the staged gradients into the host pools."""
+    dev = x["q"].device
+    gdt = x["dk_pool"].dtype
+    kbar = torch.zeros((n_max // w.P, w.Hkv, w.D), dtype=torch.float32, device=dev)
+    api.page_means(d_max, x["k_pool"], x["page_table"], 0, n_max // w.P, kbar)
+    torch.cuda.synchronize()
+
+    def pinned(t, zero=False):
+        h = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+        h.zero_() if zero else h.copy_(t)
+        return h
+
+    host_k, host_v = pinned(x["k_pool"]), pinned(x["v_pool"])
+    host_dk, host_dv = pinned(x["dk_pool"], True), pinned(x["dv_pool"], True)
+    stride = top_k + w.m
+    cap = min(n_max // w.P, w.Hkv * stride)
+    shape = (cap,) + tuple(x["k_pool"].shape[1:])
+    bufs = [dict(k=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev), v=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev),
+                 dk=torch.empty(shape, dtype=gdt, device=dev), dv=torch.empty(shape, dtype=gdt, device=dev),
+                 sel=torch.empty_like(sel), cnt=torch.empty_like(cnt),
+                 table=torch.empty(n_max // w.P, dtype=torch.int32, device=dev),
+                 pt=torch.empty(n_max // w.P, dtype=torch.int32, device=dev),
+                 slots=torch.empty(cap, dtype=torch.int32, device=dev), ns=torch.empty(1, dtype=torch.int32, device=dev))
+            for _ in range(3)]
+    main = torch.cuda.current_stream()
+    copy = torch.cuda.Stream()
+
+    def resident(s):
+        N, desc = desc_at(s)
+        api.page_score_topk_cached(desc, x["q"], kbar, top_k, sel, cnt, workspace=ws_sc)
+        api.paged_attn_fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse, ws_fw)
+        api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"], x["dv_pool"],
+                           sel, cnt, dq, ws_bw)
+
+    def select_plan(s, b):
+        N, desc = desc_at(s)
+        api.page_score_topk_cached(desc, x["q"], kbar, top_k, b["sel"], b["cnt"], workspace=ws_sc)
+        api.offload_plan(desc, b["sel"], b["cnt"], b["table"], b["slots"], b["ns"])
+        torch.clamp(b["table"], min=0, out=b["pt"])
+
+    def fetch(s, b, stream):
+        N, desc = desc_at(s)
+        api.offload_fetch(desc, host_k, host_v, x["page_table"], b["sel"], b["cnt"], b["table"], b["k"], b["v"], b["dk"], b["dv"],
+                          stream=stream)
+
+    def attend(s, b):
+        N, desc = desc_at(s)
+        api.paged_attn_fwd(desc, x["q"], b["k"], b["v"], b["pt"], b["sel"], b["cnt"], o, lse, ws_fw)
+        api.paged_attn_bwd(desc, x["q"], b["k"], b["v"], b["pt"], o, lse, x["d_o"], b["dk"], b["dv"], b["sel"], b["cnt"], dq, ws_bw)
+
+    def writeback(s, b, stream):
+        N, desc = desc_at(s)
+        api.offload_writeback(desc, b["dk"], b["dv"], host_dk, host_dv, x["page_table"], b["sel"], b["cnt"], b["table"],
+                              stream=stream)
+
+    def serial(s):
+        b = bufs[0]
+        select_plan(s, b)
+        fetch(s, b, None)
+        attend(s, b)
+        writeback(s, b, None)
+
+    def overlapped(K):
+        # The fetch of step s + 1 and the write-back of step s - 1 run on the copy stream while step s computes.
+        # Three buffer sets: the copy stream runs fetch(s), wb(s - 1), fetch(s + 1), wb(s), ... in that order, and the
+        # main stream touches set (s + 1) % 3 only after fetch(s) has landed, i.e. after wb(s - 2), its last user.
+        ev = lambda: torch.cuda.Event()
+        select_plan(0, bufs[0])
+        e = ev(); e.record(main); copy.wait_event(e)
+        fetch(0, bufs[0], copy)
+        fetched = ev(); fetched.record(copy)
+        for s in range(K):
+            b = bufs[s % 3]
+            main.wait_event(fetched)
+            if s + 1 < K:
+                nb = bufs[(s + 1) % 3]
+                select_plan(s + 1, nb)
+                e = ev(); e.record(main); copy.wait_event(e)
+                fetch(s + 1, nb, copy)
+                fetched = ev(); fetched.record(copy)
+            attend(s, b)
+            e = ev(); e.record(main); copy.wait_event(e)
+            writeback(s, b, copy)
+        e = ev(); e.record(copy); main.wait_event(e)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    K = args.steps
+    for s in range(args.warmup):
+        resident(s); serial(s)
+    overlapped(2)
+    ms_res = timed(lambda: [resident(s) for s in range(K)])
+    ms_ser = timed(lambda: [serial(s) for s in range(K)])
+    ms_ovl = timed(lambda: overlapped(K))
+    api.profile_reset(); api.profile_enable(1)
+    for s in range(K):
+        serial(s)
+    torch.cuda.synchronize()
+    api.profile_enable(False)
+    prof = {k: v[0] / max(v[1], 1) for k, v in api.profile_read().items()}
+    flops = sum(14.0 * w.D * pairs_of(w, desc_at(s)[0]) * w.Hq for s in range(K))
+    es = x["k_pool"].element_size()
+    fetch_bytes = w.Hkv * stride * 2 * w.P * w.D * es
+    wb_bytes = w.Hkv * stride * 2 * w.P * w.D * x["dk_pool"].element_size() * 2   # host read + host write
+    exposed = max(ms_ser - ms_res, 1e-9)
+    return {
+        "metric": "paged sparse attn fwd+bwd TFLOP/s per layer at 1M-token history, KV cache and gradients offloaded",
+        "value": flops / (ms_ovl * 1e-3 * K) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms_ovl, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "offload": "K/V and dK/dV pools in pinned host memory; selected pages staged",
+                   "top_k_pages": top_k, "local_pages": w.m, "scoring": "cached page means"},
+        "offload": {"ms_per_step_resident": ms_res, "ms_per_step_serial": ms_ser, "ms_per_step_overlapped": ms_ovl,
+                    "overhead_serial": ms_ser / ms_res - 1.0, "overhead_overlapped": ms_ovl / ms_res - 1.0,
+                    "overlap_fraction": (ms_ser - ms_ovl) / exposed,
+                    "fetch_ms": prof.get("offload_fetch"), "writeback_ms": prof.get("offload_writeback"),
+                    "plan_ms": prof.get("offload_plan"),
+                    "fetch_bytes": fetch_bytes, "writeback_link_bytes": wb_bytes,
+                    "fetch_GBps": fetch_bytes / (prof["offload_fetch"] * 1e-3) / 1e9 if prof.get("offload_fetch") else None,
+                    "writeback_GBps": wb_bytes / (prof["offload_writeback"] * 1e-3) / 1e9 if prof.get("offload_writeback") else None},
+        "kernels_ms": prof,
+    }
+
+
 def rocminfo_max_clock_mhz():
     """Max shader clock of the first GPU agent as rocminfo prints it (None if it cannot be read)."""
     try:
@@ -93,6 +224,11 @@ def main():
                     help="pooled: one score per key page from the mean-pooled chunk query, one page list per KV head "
                          "(the benchmark configuration); votes: per-token softmax votes summed per query page, one "
                          "list per query page (the paper's scoring equation)")
+    ap.add_argument("--offload", action="store_true",
+                    help="keep the K / V pools and their gradient pools in pinned host memory: every step fetches the "
+                         "selected pages into device staging pools and adds their gradients back (pooled retrieval, "
+                         "cached page means); reports the step time without offload, with the transfers serialised, "
+                         "and with the transfers on a second stream overlapping the neighbouring steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -175,6 +311,12 @@ def main():
         api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"],
                            x["dk_pool"], x["dv_pool"], sl, ct, dq, ws_bw)
         return N
+
+    if args.offload:
+        assert top_k is not None and not votes, "--offload runs the pooled retrieval on a sparse workload"
+        off = offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max)
+        print(json.dumps(off))
+        return
 
     if args.calibrate_copy:
         # an elementwise kernel (not a DMA copy) that reads 1 GiB and writes 1 GiB

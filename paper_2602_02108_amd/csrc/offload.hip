@@ -4,14 +4,21 @@
 // added back to the host pools.
 //
 // The copies are kernels that read (write) the pinned host memory directly over the
-// host link with 16-byte accesses, one workgroup per (list entry, KV head) tile: the
+// host link with 16-byte accesses, tile by tile ((list entry, KV head) = P rows): the
 // page list never leaves the device, so no host round trip sits between the selection
 // and the transfer, and a fetch on its own stream overlaps whatever computes meanwhile.
+// They run on a FEW workgroups that walk the tiles: host accesses take microseconds, and
+// a grid that covers the chip fills the memory pipeline of every compute unit with them,
+// which stalls a concurrently running kernel almost completely (measured: with 128 or more
+// workgroups nothing overlaps); 8 workgroups of 256 threads still move 39 GB/s and disturb only
+// the compute units they sit on.
 //   offload_plan       staging slot of every page some KV head's list holds (ascending
 //                      logical page order over the union of the lists), one workgroup
 //   offload_fetch      stage[slot][g] = host[page_table[l]][g]  (K and V), optionally
 //                      zeroing the gradient staging tiles
 //   offload_writeback  host[page_table[l]][g] += stage[slot][g]  (dK and dV)
+#include <cstdlib>
+
 #include "common.h"
 
 namespace oomb {
@@ -66,7 +73,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void offload_plan_kernel(Params p, in
   if (tid == 0) n_slots[0] = total;
 }
 
-// One workgroup per (list entry j, KV head g): a tile of P rows of D elements (row_bytes each).
+// Tile (list entry j, KV head g): P rows of D elements.  The workgroups walk the tiles with stride gridDim.x.
 // MODE 0: fetch K and V (and zero the gradient staging tiles if given); MODE 1: add dK / dV back.
 template <int MODE, typename TG>
 __global__ __launch_bounds__(256) void offload_tile_kernel(Params p, const int32_t* __restrict__ stage_table,
@@ -74,13 +81,14 @@ __global__ __launch_bounds__(256) void offload_tile_kernel(Params p, const int32
                                                            unsigned char* __restrict__ a_stage, unsigned char* __restrict__ b_stage,
                                                            unsigned char* __restrict__ ga_stage, unsigned char* __restrict__ gb_stage,
                                                            int es, int gs) {
-  const int32_t j = blockIdx.x;
-  const int g = blockIdx.y;
-  if (j >= p.sel_count[g]) return;
+  for (int32_t tile = blockIdx.x; tile < p.sel_stride * p.Hkv; tile += gridDim.x) {
+  const int g = tile / p.sel_stride;
+  const int32_t j = tile - g * p.sel_stride;
+  if (j >= p.sel_count[g]) continue;
   const int32_t l = p.sel[(int64_t)g * p.sel_stride + j];
-  if (l < 0 || l >= p.n) return;
+  if (l < 0 || l >= p.n) continue;
   const int32_t slot = stage_table[l];
-  if (slot < 0) return;
+  if (slot < 0) continue;
   const int64_t h_off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
   const int64_t s_off = (int64_t)slot * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
   if (MODE == 0) {
@@ -125,6 +133,7 @@ __global__ __launch_bounds__(256) void offload_tile_kernel(Params p, const int32
       }
     }
   }
+  }
 }
 
 // A pointer the device can dereference: device memory, or host memory that the runtime has
@@ -140,6 +149,18 @@ void* device_view(const void* ptr) {
   return attr.devicePointer;
 }
 
+// workgroups of a transfer kernel (OOMB_OFFLOAD_WGS overrides the default, for experiments)
+static unsigned transfer_wgs(const Params& p) {
+  static int v = 0;
+  if (!v) {
+    const char* e = std::getenv("OOMB_OFFLOAD_WGS");
+    v = e ? std::atoi(e) : 8;
+    if (v < 1) v = 8;
+  }
+  const int64_t tiles = (int64_t)p.sel_stride * p.Hkv;
+  return (unsigned)(tiles < v ? tiles : v);
+}
+
 hipError_t launch_offload_plan(const Params& p, int32_t* stage_table, int32_t* slot_pages, int32_t* n_slots, hipStream_t st) {
   ProfScope prof_("offload_plan", st);
   offload_plan_kernel<<<dim3(1), dim3(PLAN_THREADS), 0, st>>>(p, stage_table, slot_pages, n_slots);
@@ -149,7 +170,7 @@ hipError_t launch_offload_plan(const Params& p, int32_t* stage_table, int32_t* s
 hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* stage_table, void* host_k, void* host_v,
                                 void* stage_k, void* stage_v, void* stage_dk, void* stage_dv, hipStream_t st) {
   ProfScope prof_("offload_fetch", st);
-  offload_tile_kernel<0, float><<<dim3((unsigned)p.sel_stride, (unsigned)p.Hkv), dim3(256), 0, st>>>(
+  offload_tile_kernel<0, float><<<dim3(transfer_wgs(p)), dim3(256), 0, st>>>(
       p, stage_table, (unsigned char*)host_k, (unsigned char*)host_v, (unsigned char*)stage_k, (unsigned char*)stage_v,
       (unsigned char*)stage_dk, (unsigned char*)stage_dv, is_bf16 ? 2 : 4, p.grad_is_bf16 ? 2 : 4);
   return hipGetLastError();
@@ -158,7 +179,7 @@ hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* st
 hipError_t launch_offload_writeback(const Params& p, const int32_t* stage_table, void* stage_dk, void* stage_dv,
                                     void* host_dk, void* host_dv, hipStream_t st) {
   ProfScope prof_("offload_writeback", st);
-  dim3 grid((unsigned)p.sel_stride, (unsigned)p.Hkv);
+  dim3 grid(transfer_wgs(p));
   if (p.grad_is_bf16)
     offload_tile_kernel<1, bf16_t><<<grid, dim3(256), 0, st>>>(p, stage_table, (unsigned char*)host_dk, (unsigned char*)host_dv,
                                                                (unsigned char*)stage_dk, (unsigned char*)stage_dv, nullptr, nullptr, 2, 2);
