@@ -72,10 +72,10 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restri
 // ---------------------------------------------------------------------------------
 // dQ.  LDS: two stages of {K natural half tile, V natural half tile, K transposed
 // half tile}, 16 KiB each.  One barrier per half tile of 64 keys; the next half tile
-// is fetched into registers at the top of an iteration and written to the other
-// stage at its bottom.  The natural tiles of both stages sit in the lower 64 KiB and
-// the transposed tiles above them, so that every operand address is a loop-invariant
-// register plus an immediate offset.
+// is copied from the pre-laid-out images into the other stage with direct global ->
+// LDS loads while the current one is consumed.  The natural tiles of both stages sit
+// in the lower 64 KiB and the transposed tiles above them, so that every operand
+// address is a loop-invariant register plus an immediate offset.
 constexpr int DQ_LDS = 6 * 16384;
 constexpr int DQ_KT = 4 * 16384;  // first transposed tile
 

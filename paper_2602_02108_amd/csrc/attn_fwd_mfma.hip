@@ -1,23 +1,27 @@
 // Paged attention forward with bf16 MFMA (paper Sec. 4.1 operator over the
 // selected pages of Sec. 4.2), page size 128, head dim 128.
 //
-// A workgroup of 8 waves owns 8 consecutive blocks of one KV head's "row space":
+// A workgroup of 8 waves owns up to 8 consecutive blocks of one KV head's "row space":
 // block b = tb * G + hd is the 32 consecutive chunk tokens 32 tb .. 32 tb + 31 of
 // query head g G + hd, i.e. the G query heads of the group interleaved block by
 // block, so the K/V tiles staged in LDS are shared by all query heads of the
 // group and a workgroup's rows span at most three token blocks (short causal
 // diagonal).  Each wave keeps its 32 query rows (as the B operand of
-// S^T = K Q^T) and its 32 x 128 output block in registers.  Pages are processed
-// as two half tiles of 64 keys: K as a natural half tile, V as a transposed half
-// tile, both double buffered and staged through registers.  In
-// the S^T layout every lane owns one query row, so the online-softmax
-// statistics are per-lane scalars.
+// S^T = K Q^T) and its 32 x 128 output block in registers.  In the S^T layout
+// every lane owns one query row, so the online-softmax statistics are per-lane
+// scalars.
 //
-// Schedule (one barrier per half tile t): S_t = K_t Q^T, online softmax, then
-// O += V_t P_t.  LDS operand fragments are fetched in batches of four, one batch
-// ahead of the matrix instructions that use them; the next half tile is fetched
-// from global memory into registers at the top of an iteration and written to
-// the other LDS buffer at its bottom.
+// Pages are processed as half tiles of 64 keys -- K natural, V transposed -- that
+// are copied verbatim from pre-laid-out images (kv_layout.hip) into three K and
+// three V buffers in LDS with direct global -> LDS loads, a whole iteration ahead
+// of their use; one barrier per half tile.  The arithmetic runs as a three-stage
+// software pipeline over units of 32 keys: O += V_u P_u and S_{u+2} = K_{u+2} Q^T
+// on the matrix unit while the vector unit does the online softmax of unit u + 1
+// (see "the software pipeline" below).
+//
+// The page list of a row tile is the KV head's list, or -- one list per query page
+// (Sec. 4.2, votes per query page) -- the list of the tile's query page, whose
+// entries name their K/V images by position in the union of the head's lists.
 #include "mfma_common.h"
 
 namespace oomb {

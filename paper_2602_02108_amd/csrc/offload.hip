@@ -82,57 +82,57 @@ __global__ __launch_bounds__(256) void offload_tile_kernel(Params p, const int32
                                                            unsigned char* __restrict__ ga_stage, unsigned char* __restrict__ gb_stage,
                                                            int es, int gs) {
   for (int32_t tile = blockIdx.x; tile < p.sel_stride * p.Hkv; tile += gridDim.x) {
-  const int g = tile / p.sel_stride;
-  const int32_t j = tile - g * p.sel_stride;
-  if (j >= p.sel_count[g]) continue;
-  const int32_t l = p.sel[(int64_t)g * p.sel_stride + j];
-  if (l < 0 || l >= p.n) continue;
-  const int32_t slot = stage_table[l];
-  if (slot < 0) continue;
-  const int64_t h_off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
-  const int64_t s_off = (int64_t)slot * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
-  if (MODE == 0) {
-    const int gran = p.D * es / 16;  // 16-byte granules per token row
-    for (int x = threadIdx.x; x < p.P * gran; x += 256) {
-      const int t = x / gran, c = x - t * gran;
-      const int64_t ho = (h_off + (int64_t)t * p.pool_tok_stride) * es + 16 * c;
-      const int64_t so = (s_off + (int64_t)t * p.pool_tok_stride) * es + 16 * c;
-      *reinterpret_cast<uint4*>(a_stage + so) = *reinterpret_cast<const uint4*>(a_host + ho);
-      *reinterpret_cast<uint4*>(b_stage + so) = *reinterpret_cast<const uint4*>(b_host + ho);
-    }
-    if (ga_stage) {
-      const int ggran = p.D * gs / 16;
+    const int g = tile / p.sel_stride;
+    const int32_t j = tile - g * p.sel_stride;
+    if (j >= p.sel_count[g]) continue;
+    const int32_t l = p.sel[(int64_t)g * p.sel_stride + j];
+    if (l < 0 || l >= p.n) continue;
+    const int32_t slot = stage_table[l];
+    if (slot < 0) continue;
+    const int64_t h_off = (int64_t)p.page_table[l] * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
+    const int64_t s_off = (int64_t)slot * p.pool_page_stride + (int64_t)g * p.pool_head_stride;
+    if (MODE == 0) {
+      const int gran = p.D * es / 16;  // 16-byte granules per token row
+      for (int x = threadIdx.x; x < p.P * gran; x += 256) {
+        const int t = x / gran, c = x - t * gran;
+        const int64_t ho = (h_off + (int64_t)t * p.pool_tok_stride) * es + 16 * c;
+        const int64_t so = (s_off + (int64_t)t * p.pool_tok_stride) * es + 16 * c;
+        *reinterpret_cast<uint4*>(a_stage + so) = *reinterpret_cast<const uint4*>(a_host + ho);
+        *reinterpret_cast<uint4*>(b_stage + so) = *reinterpret_cast<const uint4*>(b_host + ho);
+      }
+      if (ga_stage) {
+        const int ggran = p.D * gs / 16;
+        for (int x = threadIdx.x; x < p.P * ggran; x += 256) {
+          const int t = x / ggran, c = x - t * ggran;
+          const int64_t so = (s_off + (int64_t)t * p.pool_tok_stride) * gs + 16 * c;
+          *reinterpret_cast<uint4*>(ga_stage + so) = make_uint4(0, 0, 0, 0);
+          *reinterpret_cast<uint4*>(gb_stage + so) = make_uint4(0, 0, 0, 0);
+        }
+      }
+    } else {
+      constexpr int EPG = 16 / (int)sizeof(TG);  // elements per granule
+      const int ggran = p.D / EPG;
       for (int x = threadIdx.x; x < p.P * ggran; x += 256) {
         const int t = x / ggran, c = x - t * ggran;
-        const int64_t so = (s_off + (int64_t)t * p.pool_tok_stride) * gs + 16 * c;
-        *reinterpret_cast<uint4*>(ga_stage + so) = make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4*>(gb_stage + so) = make_uint4(0, 0, 0, 0);
-      }
-    }
-  } else {
-    constexpr int EPG = 16 / (int)sizeof(TG);  // elements per granule
-    const int ggran = p.D / EPG;
-    for (int x = threadIdx.x; x < p.P * ggran; x += 256) {
-      const int t = x / ggran, c = x - t * ggran;
-      const int64_t ho = h_off + (int64_t)t * p.pool_tok_stride + EPG * c;
-      const int64_t so = s_off + (int64_t)t * p.pool_tok_stride + EPG * c;
-#pragma unroll
-      for (int which = 0; which < 2; ++which) {
-        TG* hp = (TG*)(which ? b_host : a_host) + ho;
-        const TG* sp = (const TG*)(which ? b_stage : a_stage) + so;
-        uint4 hv = *reinterpret_cast<const uint4*>(hp);
-        const uint4 sv = *reinterpret_cast<const uint4*>(sp);
-        TG* he = reinterpret_cast<TG*>(&hv);
-        const TG* se = reinterpret_cast<const TG*>(&sv);
-#pragma unroll
-        for (int e = 0; e < EPG; ++e) {
-          float sum = Elem<TG>::load(he + e) + Elem<TG>::load(se + e);
-          Elem<TG>::store(he + e, sum);
+        const int64_t ho = h_off + (int64_t)t * p.pool_tok_stride + EPG * c;
+        const int64_t so = s_off + (int64_t)t * p.pool_tok_stride + EPG * c;
+  #pragma unroll
+        for (int which = 0; which < 2; ++which) {
+          TG* hp = (TG*)(which ? b_host : a_host) + ho;
+          const TG* sp = (const TG*)(which ? b_stage : a_stage) + so;
+          uint4 hv = *reinterpret_cast<const uint4*>(hp);
+          const uint4 sv = *reinterpret_cast<const uint4*>(sp);
+          TG* he = reinterpret_cast<TG*>(&hv);
+          const TG* se = reinterpret_cast<const TG*>(&sv);
+  #pragma unroll
+          for (int e = 0; e < EPG; ++e) {
+            float sum = Elem<TG>::load(he + e) + Elem<TG>::load(se + e);
+            Elem<TG>::store(he + e, sum);
+          }
+          *reinterpret_cast<uint4*>(hp) = hv;
         }
-        *reinterpret_cast<uint4*>(hp) = hv;
       }
     }
-  }
   }
 }
 

@@ -123,43 +123,44 @@ __global__ __launch_bounds__(VT_THREADS) void vote_pass_kernel(Params p, const u
         *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + lq) * 4)) = 0.f;
         *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + 32 + lq) * 4)) = 0.f;
       }
-    } else
+    } else {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      f32x16 s;
+      for (int u = 0; u < 2; ++u) {
+        f32x16 s;
 #pragma unroll
-      for (int x = 0; x < 16; ++x) s[x] = 0.f;
+        for (int x = 0; x < 16; ++x) s[x] = 0.f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(smem + (ka[j] + (buf * 16384 + u * 8192))));
-        s = PASS == 1 ? mfma32(kf, qf[j], s) : mfma32(qf[j], kf, s);
-      }
-      if (PASS == 1) {
-        // s[x]: page 64 t + 32 u + 8 (x / 4) + 4 hh + x % 4, this lane's row
-        if (t == n_ht - 1) {
-          const int64_t first = (int64_t)64 * t + 32 * u + 4 * hh;
-#pragma unroll
-          for (int x = 0; x < 16; ++x)
-            if (first + 8 * (x >> 2) + (x & 3) >= p.n_past) s[x] = -INFINITY;
+        for (int j = 0; j < 8; ++j) {
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(smem + (ka[j] + (buf * 16384 + u * 8192))));
+          s = PASS == 1 ? mfma32(kf, qf[j], s) : mfma32(qf[j], kf, s);
         }
-        float mx = s[0];
+        if (PASS == 1) {
+          // s[x]: page 64 t + 32 u + 8 (x / 4) + 4 hh + x % 4, this lane's row
+          if (t == n_ht - 1) {
+            const int64_t first = (int64_t)64 * t + 32 * u + 4 * hh;
 #pragma unroll
-        for (int x = 1; x < 16; ++x) mx = fmaxf(mx, s[x]);
-        mx = half_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float mc = m_new * c;
-        float sum = 0.f;
+            for (int x = 0; x < 16; ++x)
+              if (first + 8 * (x >> 2) + (x & 3) >= p.n_past) s[x] = -INFINITY;
+          }
+          float mx = s[0];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -mc));
-        l_run = l_run * __builtin_amdgcn_exp2f((m_run - m_new) * c) + sum;
-        m_run = m_new;
-      } else {
-        // s[x]: row 8 (x / 4) + 4 hh + x % 4 of this wave, page 64 t + 32 u + lq
-        float col = 0.f;
+          for (int x = 1; x < 16; ++x) mx = fmaxf(mx, s[x]);
+          mx = half_max(mx);
+          const float m_new = fmaxf(m_run, mx);
+          const float mc = m_new * c;
+          float sum = 0.f;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) col += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -lse_r[x]));
-        col = half_sum(col);
-        if (hh == 0) *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + 32 * u + lq) * 4)) = col;
+          for (int x = 0; x < 16; ++x) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -mc));
+          l_run = l_run * __builtin_amdgcn_exp2f((m_run - m_new) * c) + sum;
+          m_run = m_new;
+        } else {
+          // s[x]: row 8 (x / 4) + 4 hh + x % 4 of this wave, page 64 t + 32 u + lq
+          float col = 0.f;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) col += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], c, -lse_r[x]));
+          col = half_sum(col);
+          if (hh == 0) *reinterpret_cast<float*>(smem + (VT_RED + ((buf * 8 + wave) * 64 + 32 * u + lq) * 4)) = col;
+        }
       }
     }
     wait_copies<0>();

@@ -139,8 +139,8 @@ def test_votes_are_deterministic():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
 
 
-def _oracle_lists_of_head(w, hx, okb, g0, top_k):
-    """The oracle's votes and lists of every query page of KV head g0.  vote[g0][tau] depends only on
+def _oracle_lists_of_head(w, hx, okb, g0, top_k, taus=None):
+    """The oracle's votes and lists of every query page (or of the query pages `taus`) of KV head g0.  vote[g0][tau] depends only on
     the rows of (g0, tau) and on the means of head g0, so each query page is a one-page problem of its
     own; they run side by side in threads (the C function releases the interpreter lock)."""
     from concurrent.futures import ThreadPoolExecutor
@@ -154,12 +154,14 @@ def _oracle_lists_of_head(w, hx, okb, g0, top_k):
         s, c, v = orc.page_vote_topk(sub, qs, kb, top_k)
         return s[0, 0, : c[0, 0] - 1], v[0, 0]
 
+    taus = list(range(w.m)) if taus is None else list(taus)
     with ThreadPoolExecutor(max_workers=min(16, orc.num_threads())) as ex:
-        res = list(ex.map(one, range(w.m)))
+        res = list(ex.map(one, taus))
     sel = np.full((w.m, top_k + w.m), -1, np.int32)
     cnt = np.zeros(w.m, np.int32)
-    votes = np.stack([r[1] for r in res])
-    for tau, (past, _) in enumerate(res):
+    votes = np.zeros((w.m, w.n_past))
+    for tau, (past, v) in zip(taus, res):
+        votes[tau] = v
         lst = list(past) + list(range(w.n_past, w.n_past + tau + 1))
         sel[tau, : len(lst)] = lst
         cnt[tau] = len(lst)
@@ -210,3 +212,48 @@ def test_votes_path_full_size():
     untouched = np.setdiff1d(np.arange(w.n_phys), hx["page_table"][union])
     idx = torch.as_tensor(untouched, device="cuda")
     assert not res["dk_pool"][idx, g0].any() and not res["dv_pool"][idx, g0].any()
+
+
+def test_votes_path_4m_stress():
+    """4M-token history, chunk 8192 (64 query pages), top-k 256, bf16 gradient pool: the largest sizes.
+    Votes and lists of three sampled (KV head, query page) pairs against the oracle, rows of those
+    query pages over the oracle's lists, and the identities that hold at any size."""
+    import test_gpu_parity_full as full
+    w = WORKLOADS["qwen_sparse_4m"]
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 64 * 2 ** 30:
+        pytest.skip("needs about 64 GiB of free device memory")
+    top_k, g0 = w.top_k, 2
+    taus = [0, 37, w.m - 1]
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    sel, cnt, votes, cache = gpu_vote(w, x, top_k)
+    sh = pu.shape_of(w)
+    okb = orc.page_means(sh, hx["k_pool"], hx["page_table"], 0, w.n_past, np.zeros((w.n, w.Hkv, w.D), np.float32))
+    assert np.array_equal(cache[: w.n_past].view(np.uint32), okb[: w.n_past].view(np.uint32)), "page means differ"
+    osel_g, ocnt_g, ovotes_g = _oracle_lists_of_head(w, hx, okb, g0, top_k, taus)
+    for tau in taus:
+        err = np.abs(votes[g0, tau] - ovotes_g[tau]) / np.maximum(ovotes_g[tau], 1e-30)
+        assert err.max() < VOTE_RTOL, (tau, err.max())
+        assert cnt[g0, tau] == ocnt_g[tau]
+        if not np.array_equal(sel[g0, tau], osel_g[tau]):   # accepted only as a tie within the tolerance
+            v = ovotes_g[tau]
+            vk = np.sort(v)[::-1][top_k - 1]
+            past = sel[g0, tau, :top_k]
+            assert v[past].min() >= vk * (1 - VOTE_RTOL)
+            assert np.delete(v, past).max() <= vk * (1 + VOTE_RTOL)
+            pytest.fail(f"list of query page {tau} differs from the oracle's by a near-tie")
+    assert (np.diff(sel[:, :, :top_k], axis=2) > 0).all()
+    assert (cnt == top_k + 1 + np.arange(w.m)[None, :]).all()
+
+    res = gpu_fwd_bwd_qp(w, x, sel, cnt)
+    osel = np.full((w.Hkv, w.m, top_k + w.m), -1, np.int32)
+    ocnt = np.zeros((w.Hkv, w.m), np.int32)
+    for tau in taus:
+        osel[g0, tau], ocnt[g0, tau] = osel_g[tau], ocnt_g[tau]
+    rng = np.random.default_rng(4)
+    rows = np.array([(g0 * w.G + int(rng.integers(w.G)), tau * w.P + int(i)) for tau in taus
+                     for i in (0, 31, 32, w.P - 1, int(rng.integers(w.P)), int(rng.integers(w.P)))], dtype=np.int32)
+    full._check_rows(w, hx, res, osel, ocnt, rows)
+    full._check_identities(w, x, res)
