@@ -338,42 +338,50 @@ def attn_fwd_bwd(sh: Shape, q, k_pool, v_pool, page_table, d_o, sel=None, sel_co
 # data movement, written as plain loops over (KV head, list entry).
 
 def offload_plan(sh: Shape, sel, sel_count):
-    """Staging slots for the pages that some KV head's list holds: slots are numbered in ascending
-    logical page order over the union of the lists.  Returns (stage_table [n] int32, -1 for pages that
-    are not staged; slot_pages [n_slots] int32, the logical page of every slot)."""
+    """Staging slots for the pages that some list holds: slots are numbered in ascending logical page
+    order over the union of all lists.  sel is [Hkv][stride] (one list per KV head) or [Hkv][m][stride] (one
+    per KV head and query page), sel_count the matching [Hkv] / [Hkv][m].  Returns (stage_table [n] int32,
+    -1 for pages that are not staged; slot_pages [n_slots] int32, the logical page of every slot;
+    head_mask [n] uint32, bit g set iff some list of KV head g holds the page)."""
     sel = _i32(sel)
     cnt = _i32(sel_count)
-    held = np.zeros(sh.n, dtype=bool)
+    assert sel.ndim in (2, 3) and cnt.shape == sel.shape[:-1] and sh.Hkv <= 32
+    head_mask = np.zeros(sh.n, dtype=np.uint32)
     for g in range(sh.Hkv):
-        held[sel[g, : cnt[g]]] = True
-    slot_pages = np.flatnonzero(held).astype(np.int32)
+        lists = sel[g][None] if sel.ndim == 2 else sel[g]
+        counts = cnt[g][None] if sel.ndim == 2 else cnt[g]
+        for lst, c in zip(lists, counts):
+            for l in lst[:c]:
+                head_mask[l] |= np.uint32(1 << g)
+    slot_pages = np.flatnonzero(head_mask).astype(np.int32)
     stage_table = np.full(sh.n, -1, dtype=np.int32)
     stage_table[slot_pages] = np.arange(len(slot_pages), dtype=np.int32)
-    return stage_table, slot_pages
+    return stage_table, slot_pages, head_mask
 
 
-def offload_fetch(sh: Shape, host_k, host_v, page_table, sel, sel_count, stage_table, stage_k, stage_v):
-    """stage[stage_table[l]][g] = host[page_table[l]][g] for every page l in the list of KV head g (K and V);
-    nothing else of the staging pools is written.  Works on copies, returns (stage_k, stage_v)."""
-    sel, cnt, pt = _i32(sel), _i32(sel_count), _i32(page_table)
+def offload_fetch(sh: Shape, host_k, host_v, page_table, slot_pages, head_mask, stage_k, stage_v):
+    """stage[s][g] = host[page_table[l]][g] for every slot s (page l = slot_pages[s]) and every KV head g
+    whose bit is set in head_mask[l] (K and V); nothing else of the staging pools is written.  Works on
+    copies, returns (stage_k, stage_v)."""
+    pt = _i32(page_table)
     stage_k, stage_v = stage_k.copy(), stage_v.copy()
-    for g in range(sh.Hkv):
-        for j in range(cnt[g]):
-            l = sel[g, j]
-            stage_k[stage_table[l], g] = host_k[pt[l], g]
-            stage_v[stage_table[l], g] = host_v[pt[l], g]
+    for s, l in enumerate(slot_pages):
+        for g in range(sh.Hkv):
+            if (int(head_mask[l]) >> g) & 1:
+                stage_k[s, g] = host_k[pt[l], g]
+                stage_v[s, g] = host_v[pt[l], g]
     return stage_k, stage_v
 
 
-def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_table, sel, sel_count, stage_table):
-    """host[page_table[l]][g] += stage[stage_table[l]][g] for every page l in the list of KV head g (dK and
-    dV), in the arithmetic of the host pool's dtype (float32 here; callers with bf16 pools round the sum).
-    Works on copies, returns (host_dk, host_dv)."""
-    sel, cnt, pt = _i32(sel), _i32(sel_count), _i32(page_table)
+def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_table, slot_pages, head_mask):
+    """host[page_table[l]][g] += stage[s][g] for the same (s, g) (dK and dV), in the arithmetic of the host
+    pool's dtype (float32 here; callers with bf16 pools round the sum).  Works on copies, returns
+    (host_dk, host_dv)."""
+    pt = _i32(page_table)
     host_dk, host_dv = host_dk.copy(), host_dv.copy()
-    for g in range(sh.Hkv):
-        for j in range(cnt[g]):
-            l = sel[g, j]
-            host_dk[pt[l], g] = host_dk[pt[l], g] + stage_dk[stage_table[l], g]
-            host_dv[pt[l], g] = host_dv[pt[l], g] + stage_dv[stage_table[l], g]
+    for s, l in enumerate(slot_pages):
+        for g in range(sh.Hkv):
+            if (int(head_mask[l]) >> g) & 1:
+                host_dk[pt[l], g] = host_dk[pt[l], g] + stage_dk[s, g]
+                host_dv[pt[l], g] = host_dv[pt[l], g] + stage_dv[s, g]
     return host_dk, host_dv
