@@ -60,7 +60,7 @@ def cpu_baseline(w, x, sample_tokens):
             "seconds": t2 - t0}
 
 
-def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max):
+def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max, votes):
     """Step = cached-means selection -> staging plan -> fetch of the selected pages from pinned host pools ->
     forward + backward on the staging pools -> write-back of the staged gradients into the host pools."""
     dev = x["q"].device
@@ -77,45 +77,45 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
     host_k, host_v = pinned(x["k_pool"]), pinned(x["v_pool"])
     host_dk, host_dv = pinned(x["dk_pool"], True), pinned(x["dv_pool"], True)
     stride = top_k + w.m
-    cap = min(n_max // w.P, w.Hkv * stride)
+    cap = min(n_max // w.P, sel.numel())
+    select = (lambda desc, s_, c_: api.page_vote_topk(desc, x["q"], kbar, top_k, s_, c_, workspace=ws_sc)) if votes else \
+        (lambda desc, s_, c_: api.page_score_topk_cached(desc, x["q"], kbar, top_k, s_, c_, workspace=ws_sc))
+    fwd = api.paged_attn_fwd_qp if votes else api.paged_attn_fwd
+    bwd = api.paged_attn_bwd_qp if votes else api.paged_attn_bwd
     shape = (cap,) + tuple(x["k_pool"].shape[1:])
     bufs = [dict(k=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev), v=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev),
                  dk=torch.empty(shape, dtype=gdt, device=dev), dv=torch.empty(shape, dtype=gdt, device=dev),
-                 sel=torch.empty_like(sel), cnt=torch.empty_like(cnt),
-                 table=torch.empty(n_max // w.P, dtype=torch.int32, device=dev),
-                 pt=torch.empty(n_max // w.P, dtype=torch.int32, device=dev),
-                 slots=torch.empty(cap, dtype=torch.int32, device=dev), ns=torch.empty(1, dtype=torch.int32, device=dev))
+                 sel=torch.empty_like(sel), cnt=torch.empty_like(cnt), plan=api.OffloadPlan(d_max, cap, dev),
+                 pt=torch.empty(n_max // w.P, dtype=torch.int32, device=dev))
             for _ in range(3)]
     main = torch.cuda.current_stream()
     copy = torch.cuda.Stream()
 
     def resident(s):
         N, desc = desc_at(s)
-        api.page_score_topk_cached(desc, x["q"], kbar, top_k, sel, cnt, workspace=ws_sc)
-        api.paged_attn_fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse, ws_fw)
-        api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"], x["dv_pool"],
-                           sel, cnt, dq, ws_bw)
+        select(desc, sel, cnt)
+        fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse, ws_fw)
+        bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"], x["dv_pool"],
+            sel, cnt, dq, ws_bw)
 
     def select_plan(s, b):
         N, desc = desc_at(s)
-        api.page_score_topk_cached(desc, x["q"], kbar, top_k, b["sel"], b["cnt"], workspace=ws_sc)
-        api.offload_plan(desc, b["sel"], b["cnt"], b["table"], b["slots"], b["ns"])
-        torch.clamp(b["table"], min=0, out=b["pt"])
+        select(desc, b["sel"], b["cnt"])
+        api.offload_plan(desc, b["sel"], b["cnt"], b["plan"])
+        torch.clamp(b["plan"].stage_table, min=0, out=b["pt"])
 
     def fetch(s, b, stream):
         N, desc = desc_at(s)
-        api.offload_fetch(desc, host_k, host_v, x["page_table"], b["sel"], b["cnt"], b["table"], b["k"], b["v"], b["dk"], b["dv"],
-                          stream=stream)
+        api.offload_fetch(desc, host_k, host_v, x["page_table"], b["plan"], b["k"], b["v"], b["dk"], b["dv"], stream=stream)
 
     def attend(s, b):
         N, desc = desc_at(s)
-        api.paged_attn_fwd(desc, x["q"], b["k"], b["v"], b["pt"], b["sel"], b["cnt"], o, lse, ws_fw)
-        api.paged_attn_bwd(desc, x["q"], b["k"], b["v"], b["pt"], o, lse, x["d_o"], b["dk"], b["dv"], b["sel"], b["cnt"], dq, ws_bw)
+        fwd(desc, x["q"], b["k"], b["v"], b["pt"], b["sel"], b["cnt"], o, lse, ws_fw)
+        bwd(desc, x["q"], b["k"], b["v"], b["pt"], o, lse, x["d_o"], b["dk"], b["dv"], b["sel"], b["cnt"], dq, ws_bw)
 
     def writeback(s, b, stream):
         N, desc = desc_at(s)
-        api.offload_writeback(desc, b["dk"], b["dv"], host_dk, host_dv, x["page_table"], b["sel"], b["cnt"], b["table"],
-                              stream=stream)
+        api.offload_writeback(desc, b["dk"], b["dv"], host_dk, host_dv, x["page_table"], b["plan"], stream=stream)
 
     def serial(s):
         b = bufs[0]
@@ -169,8 +169,11 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
     prof = {k: v[0] / max(v[1], 1) for k, v in api.profile_read().items()}
     flops = sum(14.0 * w.D * pairs_of(w, desc_at(s)[0]) * w.Hq for s in range(K))
     es = x["k_pool"].element_size()
-    fetch_bytes = w.Hkv * stride * 2 * w.P * w.D * es
-    wb_bytes = w.Hkv * stride * 2 * w.P * w.D * x["dk_pool"].element_size() * 2   # host read + host write
+    # (page, KV head) tiles moved by the last step: the set bits of the plan's head mask
+    mask = bufs[0]["plan"].head_mask.cpu().numpy().view("uint32")
+    tiles = int(sum(bin(int(v)).count("1") for v in mask[mask != 0]))
+    fetch_bytes = tiles * 2 * w.P * w.D * es
+    wb_bytes = tiles * 2 * w.P * w.D * x["dk_pool"].element_size() * 2   # host read + host write
     exposed = max(ms_ser - ms_res, 1e-9)
     return {
         "metric": "paged sparse attn fwd+bwd TFLOP/s per layer at 1M-token history, KV cache and gradients offloaded",
@@ -178,7 +181,9 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
         "ms_per_step": ms_ovl, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "offload": "K/V and dK/dV pools in pinned host memory; selected pages staged",
-                   "top_k_pages": top_k, "local_pages": w.m, "scoring": "cached page means"},
+                   "top_k_pages": top_k, "local_pages": w.m, "scoring": "cached page means",
+                   "retrieval": "softmax votes, one list per query page" if votes else
+                                "pooled query score, one list per KV head", "tiles_moved_per_step": tiles},
         "offload": {"ms_per_step_resident": ms_res, "ms_per_step_serial": ms_ser, "ms_per_step_overlapped": ms_ovl,
                     "overhead_serial": ms_ser / ms_res - 1.0, "overhead_overlapped": ms_ovl / ms_res - 1.0,
                     "overlap_fraction": (ms_ser - ms_ovl) / exposed,
@@ -313,8 +318,9 @@ def main():
         return N
 
     if args.offload:
-        assert top_k is not None and not votes, "--offload runs the pooled retrieval on a sparse workload"
-        off = offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max)
+        assert top_k is not None, "--offload needs a sparse workload"
+        off = offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, ws_sc, ws_fw, ws_bw, n_max, d_max,
+                            votes)
         print(json.dumps(off))
         return
 

@@ -247,41 +247,46 @@ oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_page
  * pages a chunk needs are transferred asynchronously; pinned memory and dedicated streams).
  * The host pools are PINNED HOST memory that the device can address (hipHostMalloc, or a
  * pinned torch tensor); they have the layout and strides of the descriptor's pools.  The
- * transfers are kernels that read / write that memory directly, one workgroup per (list
- * entry, KV head) tile, enqueued on hip_stream like everything else: put them on a stream of
- * their own to overlap them with computation, and order them against the attention calls
- * with events.  The page lists are the per-KV-head lists of oomb_page_score_topk*.
+ * transfers are kernels that read / write that memory directly, one (page, KV head) tile
+ * after the other on a few workgroups, enqueued on hip_stream like everything else: put them
+ * on a stream of their own to overlap them with computation, and order them against the
+ * attention calls with events.
  *
- * oomb_offload_plan: staging slots for the pages that some KV head's list holds, numbered in
- *   ascending logical page order over the union of the lists.
- *     stage_table [n] int32 device, out: slot of a staged logical page, -1 otherwise
- *     slot_pages  [min(n, Hkv * sel_stride)] int32 device, out: logical page of every slot
+ * oomb_offload_plan: which pages the lists hold, and a staging slot for each.
+ *     sel_pages / sel_count: lists_per_head = 1: [Hkv][sel_stride] / [Hkv] (oomb_page_score_topk*);
+ *                            lists_per_head = m: [Hkv][m][sel_stride] / [Hkv][m] (oomb_page_vote_topk)
+ *     head_mask   [n] uint32 device, out: bit g set iff some list of KV head g holds the page
+ *     stage_table [n] int32 device, out: slot of a held page, numbered in ascending logical page
+ *                 order over all held pages; -1 otherwise
+ *     slot_pages  [min(n, Hkv * lists_per_head * sel_stride)] int32 device, out: page of every slot
  *     n_slots     [1] int32 device, out
- * oomb_offload_fetch: for every page l in the list of KV head g,
- *     stage_k / stage_v [stage_table[l]][g][:][:] = host_k / host_v [page_table[l]][g][:][:]
+ *   Hkv <= 32 (else OOMB_ERR_UNSUPPORTED).
+ * oomb_offload_fetch: for every slot s < min(n_slots, stage_capacity), l = slot_pages[s], and every
+ *   KV head g with bit g of head_mask[l] set,
+ *     stage_k / stage_v [s][g][:][:] = host_k / host_v [page_table[l]][g][:][:]
  *   bit for bit; if stage_dk / stage_dv are given (both or neither) the same tiles of the
- *   gradient staging pools are zeroed.  Staging pools: device memory, descriptor strides, at
- *   least min(n, Hkv * sel_stride) pages; tiles of a slot that belong to a KV head whose list
- *   does not hold the page are left alone and are never read by the attention kernels.
- *   The attention entry points then run on the staging pools with page_table = stage_table
- *   (their descriptor keeps num_phys_pages >= n: the bound is on the table's domain).
- * oomb_offload_writeback: for the same (l, g),
- *     host_dk / host_dv [page_table[l]][g] += stage_dk / stage_dv [stage_table[l]][g]
+ *   gradient staging pools are zeroed.  Staging pools: device memory, descriptor strides,
+ *   stage_capacity pages; the other tiles of a slot are left alone and are never read by the
+ *   attention kernels.  The attention entry points then run on the staging pools with
+ *   page_table = stage_table (their descriptor keeps num_phys_pages >= n: the bound is on the
+ *   table's domain).
+ * oomb_offload_writeback: for the same (s, g),
+ *     host_dk / host_dv [page_table[l]][g] += stage_dk / stage_dv [s][g]
  *   in float (rounded to the pool's dtype for bf16 pools); nothing else is written.
  * Errors: OOMB_ERR_INVALID_ARG also for a host pool that is not device-addressable memory
  * (checked with hipPointerGetAttributes before anything is launched).
  */
 oomb_status oomb_offload_plan(const oomb_attn_desc* desc, const int32_t* sel_pages, const int32_t* sel_count,
-                              int32_t sel_stride, int32_t* stage_table, int32_t* slot_pages, int32_t* n_slots,
-                              void* hip_stream);
+                              int32_t sel_stride, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
+                              uint32_t* head_mask, int32_t* n_slots, void* hip_stream);
 oomb_status oomb_offload_fetch(const oomb_attn_desc* desc, const void* host_k_pool, const void* host_v_pool,
-                               const int32_t* page_table, const int32_t* sel_pages, const int32_t* sel_count,
-                               int32_t sel_stride, const int32_t* stage_table, void* stage_k, void* stage_v,
+                               const int32_t* page_table, const int32_t* slot_pages, const uint32_t* head_mask,
+                               const int32_t* n_slots, int32_t stage_capacity, void* stage_k, void* stage_v,
                                void* stage_dk, void* stage_dv, void* hip_stream);
 oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage_dk, const void* stage_dv,
                                    void* host_dk_pool, void* host_dv_pool, const int32_t* page_table,
-                                   const int32_t* sel_pages, const int32_t* sel_count, int32_t sel_stride,
-                                   const int32_t* stage_table, void* hip_stream);
+                                   const int32_t* slot_pages, const uint32_t* head_mask, const int32_t* n_slots,
+                                   int32_t stage_capacity, void* hip_stream);
 
 /*
  * Benchmark aid (not part of the paper's method): per-kernel device time.  While

@@ -70,11 +70,11 @@ def lib():
         l.oomb_page_vote_topk.restype = i32
         l.oomb_page_vote_topk.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
         l.oomb_offload_plan.restype = i32
-        l.oomb_offload_plan.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp]
+        l.oomb_offload_plan.argtypes = [dp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
         l.oomb_offload_fetch.restype = i32
-        l.oomb_offload_fetch.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        l.oomb_offload_fetch.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         l.oomb_offload_writeback.restype = i32
-        l.oomb_offload_writeback.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+        l.oomb_offload_writeback.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
@@ -220,41 +220,55 @@ def _stream_of(stream, t):
     return ctypes.c_void_p(stream.cuda_stream) if stream is not None else _stream(t)
 
 
-def offload_plan(desc: AttnDesc, sel_pages, sel_count, stage_table=None, slot_pages=None, n_slots=None, stream=None):
-    """oomb_offload_plan.  Returns (stage_table [n] int32, slot_pages [min(n, Hkv * stride)] int32, n_slots [1] int32),
-    all on the device of sel_pages."""
+class OffloadPlan:
+    """Device arrays written by oomb_offload_plan (see include/oomb.h)."""
+
+    def __init__(self, desc, capacity, device):
+        n = desc.ctx_len // desc.page_size
+        self.capacity = int(capacity)
+        self.stage_table = torch.empty(n, dtype=torch.int32, device=device)
+        self.slot_pages = torch.empty(self.capacity, dtype=torch.int32, device=device)
+        self.head_mask = torch.empty(n, dtype=torch.int32, device=device)   # bit patterns of uint32
+        self.n_slots = torch.empty(1, dtype=torch.int32, device=device)
+
+
+def offload_capacity(desc: AttnDesc, sel_pages) -> int:
+    """Slots that always suffice for lists of this shape: min(n, Hkv * lists per head * row stride)."""
     n = desc.ctx_len // desc.page_size
-    stride = int(sel_pages.stride(0))
-    dev = sel_pages.device
-    if stage_table is None:
-        stage_table = torch.empty(n, dtype=torch.int32, device=dev)
-    if slot_pages is None:
-        slot_pages = torch.empty(min(n, desc.n_kv_heads * stride), dtype=torch.int32, device=dev)
-    if n_slots is None:
-        n_slots = torch.empty(1, dtype=torch.int32, device=dev)
-    st = lib().oomb_offload_plan(ctypes.byref(desc), _p(sel_pages), _p(sel_count), stride, _p(stage_table), _p(slot_pages),
-                                 _p(n_slots), _stream_of(stream, sel_pages))
+    return min(n, sel_pages.numel())
+
+
+def offload_plan(desc: AttnDesc, sel_pages, sel_count, plan: "OffloadPlan" = None, stream=None) -> "OffloadPlan":
+    """oomb_offload_plan for lists [Hkv][stride] or [Hkv][m][stride]."""
+    assert sel_pages.dim() in (2, 3) and sel_pages.is_contiguous() and sel_count.is_contiguous()
+    lists_per_head = 1 if sel_pages.dim() == 2 else int(sel_pages.shape[1])
+    if plan is None:
+        plan = OffloadPlan(desc, offload_capacity(desc, sel_pages), sel_pages.device)
+    st = lib().oomb_offload_plan(ctypes.byref(desc), _p(sel_pages), _p(sel_count), int(sel_pages.shape[-1]), lists_per_head,
+                                 _p(plan.stage_table), _p(plan.slot_pages), _p(plan.head_mask), _p(plan.n_slots),
+                                 _stream_of(stream, sel_pages))
     if st != OK:
         raise OombError(st, "oomb_offload_plan")
-    return stage_table, slot_pages, n_slots
+    return plan
 
 
-def offload_fetch(desc: AttnDesc, host_k_pool, host_v_pool, page_table, sel_pages, sel_count, stage_table, stage_k, stage_v,
+def offload_fetch(desc: AttnDesc, host_k_pool, host_v_pool, page_table, plan: "OffloadPlan", stage_k, stage_v,
                   stage_dk=None, stage_dv=None, stream=None) -> None:
-    """oomb_offload_fetch: host_*_pool are pinned host tensors (or device tensors) with the pools' layout."""
-    st = lib().oomb_offload_fetch(ctypes.byref(desc), _p(host_k_pool), _p(host_v_pool), _p(page_table), _p(sel_pages),
-                                  _p(sel_count), int(sel_pages.stride(0)), _p(stage_table), _p(stage_k), _p(stage_v),
+    """oomb_offload_fetch: host_*_pool are pinned host tensors (or device tensors) with the pools' layout; the
+    staging pools hold stage_k.shape[0] pages."""
+    st = lib().oomb_offload_fetch(ctypes.byref(desc), _p(host_k_pool), _p(host_v_pool), _p(page_table), _p(plan.slot_pages),
+                                  _p(plan.head_mask), _p(plan.n_slots), int(stage_k.shape[0]), _p(stage_k), _p(stage_v),
                                   _p(stage_dk), _p(stage_dv), _stream_of(stream, stage_k))
     if st != OK:
         raise OombError(st, "oomb_offload_fetch")
 
 
-def offload_writeback(desc: AttnDesc, stage_dk, stage_dv, host_dk_pool, host_dv_pool, page_table, sel_pages, sel_count,
-                      stage_table, stream=None) -> None:
-    """oomb_offload_writeback: host pools += the staged gradient tiles of the listed pages."""
+def offload_writeback(desc: AttnDesc, stage_dk, stage_dv, host_dk_pool, host_dv_pool, page_table, plan: "OffloadPlan",
+                      stream=None) -> None:
+    """oomb_offload_writeback: host pools += the staged gradient tiles of the held (page, KV head) pairs."""
     st = lib().oomb_offload_writeback(ctypes.byref(desc), _p(stage_dk), _p(stage_dv), _p(host_dk_pool), _p(host_dv_pool),
-                                      _p(page_table), _p(sel_pages), _p(sel_count), int(sel_pages.stride(0)),
-                                      _p(stage_table), _stream_of(stream, stage_dk))
+                                      _p(page_table), _p(plan.slot_pages), _p(plan.head_mask), _p(plan.n_slots),
+                                      int(stage_dk.shape[0]), _stream_of(stream, stage_dk))
     if st != OK:
         raise OombError(st, "oomb_offload_writeback")
 

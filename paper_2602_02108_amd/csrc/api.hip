@@ -25,11 +25,14 @@ size_t vote_workspace_bytes(const Params& p, bool is_bf16, bool force_generic);
 hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const float* kbar, int32_t top_k, int32_t* sel,
                             int32_t* sel_count, float* votes_out, void* ws, hipStream_t st);
 void* device_view(const void* ptr);
-hipError_t launch_offload_plan(const Params& p, int32_t* stage_table, int32_t* slot_pages, int32_t* n_slots, hipStream_t st);
-hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* stage_table, void* host_k, void* host_v,
-                                void* stage_k, void* stage_v, void* stage_dk, void* stage_dv, hipStream_t st);
-hipError_t launch_offload_writeback(const Params& p, const int32_t* stage_table, void* stage_dk, void* stage_dv,
-                                    void* host_dk, void* host_dv, hipStream_t st);
+hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
+                               uint32_t* head_mask, int32_t* n_slots, hipStream_t st);
+hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* slot_pages, const uint32_t* head_mask,
+                                const int32_t* n_slots, int32_t stage_cap, void* host_k, void* host_v, void* stage_k,
+                                void* stage_v, void* stage_dk, void* stage_dv, hipStream_t st);
+hipError_t launch_offload_writeback(const Params& p, const int32_t* slot_pages, const uint32_t* head_mask,
+                                    const int32_t* n_slots, int32_t stage_cap, void* stage_dk, void* stage_dv, void* host_dk,
+                                    void* host_dv, hipStream_t st);
 size_t qp_maps_bytes(const Params& p, int32_t stride);
 int32_t qp_union_cap(const Params& p, int32_t stride);
 hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st);
@@ -387,25 +390,28 @@ oomb_status oomb_paged_attn_bwd_qp(const oomb_attn_desc* desc, const void* q, co
 }
 
 oomb_status oomb_offload_plan(const oomb_attn_desc* desc, const int32_t* sel_pages, const int32_t* sel_count,
-                              int32_t sel_stride, int32_t* stage_table, int32_t* slot_pages, int32_t* n_slots,
-                              void* hip_stream) {
+                              int32_t sel_stride, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
+                              uint32_t* head_mask, int32_t* n_slots, void* hip_stream) {
   Params p{};
   oomb_status s = check_desc(desc, &p);
   if (s != OOMB_OK) return s;
-  if (!sel_pages || !sel_count || sel_stride < p.m || !stage_table || !slot_pages || !n_slots) return OOMB_ERR_INVALID_ARG;
+  if (!sel_pages || !sel_count || sel_stride < p.m || !stage_table || !slot_pages || !head_mask || !n_slots)
+    return OOMB_ERR_INVALID_ARG;
+  if (lists_per_head != 1 && lists_per_head != p.m) return OOMB_ERR_INVALID_ARG;
+  if (p.Hkv > 32 || (int64_t)lists_per_head * sel_stride > INT32_MAX) return OOMB_ERR_UNSUPPORTED;
   p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
-  hipError_t e = launch_offload_plan(p, stage_table, slot_pages, n_slots, (hipStream_t)hip_stream);
+  hipError_t e = launch_offload_plan(p, lists_per_head, stage_table, slot_pages, head_mask, n_slots, (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 
 oomb_status oomb_offload_fetch(const oomb_attn_desc* desc, const void* host_k_pool, const void* host_v_pool,
-                               const int32_t* page_table, const int32_t* sel_pages, const int32_t* sel_count,
-                               int32_t sel_stride, const int32_t* stage_table, void* stage_k, void* stage_v,
+                               const int32_t* page_table, const int32_t* slot_pages, const uint32_t* head_mask,
+                               const int32_t* n_slots, int32_t stage_capacity, void* stage_k, void* stage_v,
                                void* stage_dk, void* stage_dv, void* hip_stream) {
   Params p{};
   oomb_status s = check_desc(desc, &p);
   if (s != OOMB_OK) return s;
-  if (!host_k_pool || !host_v_pool || !page_table || !sel_pages || !sel_count || sel_stride < p.m || !stage_table ||
+  if (!host_k_pool || !host_v_pool || !page_table || !slot_pages || !head_mask || !n_slots || stage_capacity <= 0 ||
       !stage_k || !stage_v || (stage_dk == nullptr) != (stage_dv == nullptr))
     return OOMB_ERR_INVALID_ARG;
   if (!aligned16(host_k_pool) || !aligned16(host_v_pool) || !aligned16(stage_k) || !aligned16(stage_v) ||
@@ -416,21 +422,20 @@ oomb_status oomb_offload_fetch(const oomb_attn_desc* desc, const void* host_k_po
   void* hv = device_view(host_v_pool);
   if (!hk || !hv) return OOMB_ERR_INVALID_ARG;
   p.page_table = page_table;
-  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
-  hipError_t e = launch_offload_fetch(p, desc->dtype == OOMB_BF16, stage_table, hk, hv, stage_k, stage_v, stage_dk,
-                                      stage_dv, (hipStream_t)hip_stream);
+  hipError_t e = launch_offload_fetch(p, desc->dtype == OOMB_BF16, slot_pages, head_mask, n_slots, stage_capacity, hk, hv,
+                                      stage_k, stage_v, stage_dk, stage_dv, (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 
 oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage_dk, const void* stage_dv,
                                    void* host_dk_pool, void* host_dv_pool, const int32_t* page_table,
-                                   const int32_t* sel_pages, const int32_t* sel_count, int32_t sel_stride,
-                                   const int32_t* stage_table, void* hip_stream) {
+                                   const int32_t* slot_pages, const uint32_t* head_mask, const int32_t* n_slots,
+                                   int32_t stage_capacity, void* hip_stream) {
   Params p{};
   oomb_status s = check_desc(desc, &p);
   if (s != OOMB_OK) return s;
-  if (!stage_dk || !stage_dv || !host_dk_pool || !host_dv_pool || !page_table || !sel_pages || !sel_count ||
-      sel_stride < p.m || !stage_table)
+  if (!stage_dk || !stage_dv || !host_dk_pool || !host_dv_pool || !page_table || !slot_pages || !head_mask || !n_slots ||
+      stage_capacity <= 0)
     return OOMB_ERR_INVALID_ARG;
   if (!aligned16(stage_dk) || !aligned16(stage_dv) || !aligned16(host_dk_pool) || !aligned16(host_dv_pool))
     return OOMB_ERR_INVALID_ARG;
@@ -438,9 +443,8 @@ oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage
   void* hv = device_view(host_dv_pool);
   if (!hk || !hv) return OOMB_ERR_INVALID_ARG;
   p.page_table = page_table;
-  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
-  hipError_t e = launch_offload_writeback(p, stage_table, const_cast<void*>(stage_dk), const_cast<void*>(stage_dv), hk, hv,
-                                          (hipStream_t)hip_stream);
+  hipError_t e = launch_offload_writeback(p, slot_pages, head_mask, n_slots, stage_capacity, const_cast<void*>(stage_dk),
+                                          const_cast<void*>(stage_dv), hk, hv, (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

@@ -156,15 +156,19 @@ def test_offload_entry_points_validate_before_launch():
     l = api.lib()
     fake = ctypes.c_void_p(0x1000)
     m = 4096 // 128
-    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 8, fake, fake, fake, None) == api.ERR_INVALID_ARG  # stride < m
-    assert l.oomb_offload_plan(ctypes.byref(d), fake, None, 64 + m, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    # plan: row stride that cannot hold the local pages; missing counts; lists per head neither 1 nor m
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 8, 1, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, None, 64 + m, 1, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 64 + m, 3, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
     # gradient staging pools come in pairs
-    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, 64 + m, fake, fake, fake, fake, None,
+    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 640, fake, fake, fake, None,
                                 None) == api.ERR_INVALID_ARG
     # a host pool the device cannot address (here: not memory at all) is refused before any launch
-    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, 64 + m, fake, fake, fake, None, None,
+    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 640, fake, fake, None, None,
                                 None) == api.ERR_INVALID_ARG
-    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, 64 + m, fake,
+    assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 0, fake, fake, None, None,
+                                None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, 640,
                                     None) == api.ERR_INVALID_ARG
-    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, None, fake, fake, fake, fake, 64 + m, fake,
+    assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, None, fake, fake, fake, fake, fake, 640,
                                     None) == api.ERR_INVALID_ARG
