@@ -116,10 +116,12 @@ def test_sparse_full_size(name):
     boosted = set(x["boosted"].cpu().numpy().tolist())
     hit = [len(boosted & set(osel[g][:w.top_k].tolist())) for g in range(w.Hkv)]
     assert max(hit) >= min(len(boosted), w.top_k) * 0.9, hit
-    _check_rows(w, hx, res, osel, ocnt, _sample_rows(w, 160, 1))
+    _check_rows(w, hx, res, osel, ocnt, _sample_rows(w, 256, 1))
     g = 1
-    pages = [int(osel[g][0]), int(osel[g][w.top_k // 2]), int(osel[g][w.top_k]), int(osel[g][w.top_k + w.m // 2]),
-             int(osel[g][ocnt[g] - 1])]   # past pages, first / middle / last local (diagonal) page
+    # eight pages of one KV head: five past pages spread over the list, the first / a middle / the last local page
+    # (every local page holds the causal diagonal of its own query rows)
+    pages = [int(osel[g][j]) for j in (0, w.top_k // 4, w.top_k // 2, 3 * w.top_k // 4, w.top_k - 1)] + \
+            [int(osel[g][w.top_k]), int(osel[g][w.top_k + w.m // 2]), int(osel[g][ocnt[g] - 1])]
     _check_units(w, hx, res, osel, ocnt, g, pages)
     _check_identities(w, x, res)
     _untouched(w, x, res, osel, ocnt, hx["page_table"])
