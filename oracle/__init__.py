@@ -385,3 +385,48 @@ def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_tabl
                 host_dk[pt[l], g] = host_dk[pt[l], g] + stage_dk[s, g]
                 host_dv[pt[l], g] = host_dv[pt[l], g] + stage_dv[s, g]
     return host_dk, host_dv
+
+
+# ---------------------------------------------------------------------------------------------
+# Preconditions of the attention entry points (Sec. 4.1: a page table maps logical pages to distinct
+# physical pages; Sec. 4.2: the lists hold the retrieved pages and the chunk's own pages), written
+# out as plain checks.  Bits of the result:
+CHECK_TABLE_RANGE = 1      # a page-table entry outside [0, n_phys)
+CHECK_TABLE_DISTINCT = 2   # two logical pages share a physical page
+CHECK_LIST_COUNT = 4       # a list count outside [0, stride]
+CHECK_LIST_RANGE = 8       # a list entry outside [0, n)
+CHECK_LIST_ORDER = 16      # a list that is not strictly ascending
+CHECK_LIST_LOCAL = 32      # a list without the local page(s) it must hold
+
+
+def check_inputs(sh: Shape, n_phys: int, page_table, sel=None, sel_count=None) -> int:
+    """Violations (bit mask) of the documented preconditions.  sel [Hkv][stride] must hold all m local
+    pages; sel [Hkv][m][stride] must hold, in the list of query page tau, the local page n_past + tau."""
+    pt = _i32(page_table)[: sh.n]
+    bad = 0
+    in_range = (pt >= 0) & (pt < n_phys)
+    if not in_range.all():
+        bad |= CHECK_TABLE_RANGE
+    ok = pt[in_range]
+    if len(np.unique(ok)) != len(ok):
+        bad |= CHECK_TABLE_DISTINCT
+    if sel is None:
+        return bad
+    sel, cnt = _i32(sel), _i32(sel_count)
+    stride = sel.shape[-1]
+    lists = sel.reshape(-1, stride)
+    counts = cnt.reshape(-1)
+    per_head = lists.shape[0] // sh.Hkv
+    for idx, (lst, c) in enumerate(zip(lists, counts)):
+        if c < 0 or c > stride:
+            bad |= CHECK_LIST_COUNT
+            c = min(max(int(c), 0), stride)
+        e = lst[:c]
+        if ((e < 0) | (e >= sh.n)).any():
+            bad |= CHECK_LIST_RANGE
+        if (np.diff(e) <= 0).any():
+            bad |= CHECK_LIST_ORDER
+        need = range(sh.n_past, sh.n) if per_head == 1 else [sh.n_past + idx % per_head]
+        if not set(need) <= set(int(v) for v in e):
+            bad |= CHECK_LIST_LOCAL
+    return bad
