@@ -61,7 +61,8 @@ typedef enum {
   OOMB_OP_ATTN_BWD = 2,
   OOMB_OP_VOTE_TOPK = 3,   /* oomb_page_vote_topk */
   OOMB_OP_ATTN_FWD_QP = 4, /* oomb_paged_attn_fwd_qp */
-  OOMB_OP_ATTN_BWD_QP = 5  /* oomb_paged_attn_bwd_qp */
+  OOMB_OP_ATTN_BWD_QP = 5, /* oomb_paged_attn_bwd_qp */
+  OOMB_OP_CHECK_INPUTS = 6 /* oomb_check_inputs */
 } oomb_op;
 
 typedef struct {
@@ -287,6 +288,25 @@ oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage
                                    void* host_dk_pool, void* host_dv_pool, const int32_t* page_table,
                                    const int32_t* slot_pages, const uint32_t* head_mask, const int32_t* n_slots,
                                    int32_t stage_capacity, void* hip_stream);
+
+/*
+ * Debug aid: the documented preconditions of the attention entry points, checked on the device
+ * (the hot path trusts them).  Writes a bit mask to violations[0] (device, int32):
+ *   1  a page_table entry (logical pages 0 .. n-1) outside [0, num_phys_pages)
+ *   2  two logical pages mapped to the same physical page
+ *   4  a list count outside [0, sel_stride]
+ *   8  a list entry outside [0, n)
+ *   16 a list that is not strictly ascending (this also catches duplicates)
+ *   32 a list without the local pages it must hold: all m of them for lists_per_head = 1
+ *      ([Hkv][sel_stride]), page n_past + tau for the list of query page tau with
+ *      lists_per_head = m ([Hkv][m][sel_stride])
+ * sel_pages == NULL checks the page table only.  One workgroup; reads only, apart from the
+ * workspace (oomb_workspace_bytes(desc, 0, OOMB_OP_CHECK_INPUTS) = num_phys_pages int32) and
+ * violations[0].  No index is dereferenced before it has been checked.
+ */
+oomb_status oomb_check_inputs(const oomb_attn_desc* desc, const int32_t* page_table, const int32_t* sel_pages,
+                              const int32_t* sel_count, int32_t sel_stride, int32_t lists_per_head, int32_t* violations,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Benchmark aid (not part of the paper's method): per-kernel device time.  While

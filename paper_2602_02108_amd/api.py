@@ -14,14 +14,15 @@ LIB_PATH = os.path.join(_HERE, "liboomb.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
 F32, BF16 = 0, 1
-OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD, OP_VOTE_TOPK, OP_ATTN_FWD_QP, OP_ATTN_BWD_QP = range(6)
+OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD, OP_VOTE_TOPK, OP_ATTN_FWD_QP, OP_ATTN_BWD_QP, \
+    OP_CHECK_INPUTS = range(7)
 
 EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd",
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
            "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
            "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
            "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk",
-           "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback"]
+           "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback", "oomb_check_inputs"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -75,6 +76,8 @@ def lib():
         l.oomb_offload_fetch.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         l.oomb_offload_writeback.restype = i32
         l.oomb_offload_writeback.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+        l.oomb_check_inputs.restype = i32
+        l.oomb_check_inputs.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, u64, vp]
         l.oomb_status_string.restype = ctypes.c_char_p
         l.oomb_status_string.argtypes = [i32]
         l.oomb_version.restype = i32
@@ -218,6 +221,23 @@ def page_vote_topk(desc: AttnDesc, q, kbar_cache, top_k: int, sel_pages=None, se
 
 def _stream_of(stream, t):
     return ctypes.c_void_p(stream.cuda_stream) if stream is not None else _stream(t)
+
+
+def check_inputs(desc: AttnDesc, page_table, sel_pages=None, sel_count=None) -> int:
+    """oomb_check_inputs: the violation bits (0 = the documented preconditions hold).  Synchronises."""
+    dev = page_table.device
+    out = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(workspace_bytes(desc, 0, OP_CHECK_INPUTS), 256), dtype=torch.uint8, device=dev)
+    stride = lists = 0
+    if sel_pages is not None:
+        assert sel_pages.dim() in (2, 3) and sel_pages.is_contiguous() and sel_count.is_contiguous()
+        stride = int(sel_pages.shape[-1])
+        lists = 1 if sel_pages.dim() == 2 else int(sel_pages.shape[1])
+    st = lib().oomb_check_inputs(ctypes.byref(desc), _p(page_table), _p(sel_pages), _p(sel_count), stride, lists, _p(out),
+                                 _p(ws), ws.numel(), _stream(page_table))
+    if st != OK:
+        raise OombError(st, "oomb_check_inputs")
+    return int(out.item())
 
 
 class OffloadPlan:

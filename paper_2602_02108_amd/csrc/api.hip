@@ -33,6 +33,8 @@ hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* sl
 hipError_t launch_offload_writeback(const Params& p, const int32_t* slot_pages, const uint32_t* head_mask,
                                     const int32_t* n_slots, int32_t stage_cap, void* stage_dk, void* stage_dv, void* host_dk,
                                     void* host_dv, hipStream_t st);
+hipError_t launch_check_inputs(const Params& p, int64_t num_phys, int32_t lists_per_head, int32_t* marks, int32_t* out,
+                               hipStream_t st);
 size_t qp_maps_bytes(const Params& p, int32_t stride);
 int32_t qp_union_cap(const Params& p, int32_t stride);
 hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st);
@@ -148,6 +150,8 @@ size_t oomb_workspace_bytes(const oomb_attn_desc* desc, int32_t top_k, int32_t o
     case OOMB_OP_VOTE_TOPK:
       if (top_k < 0) return 0;
       return vote_workspace_bytes(p, desc->dtype == OOMB_BF16, force_generic());
+    case OOMB_OP_CHECK_INPUTS:
+      return up256((size_t)desc->num_phys_pages * sizeof(int32_t));
     case OOMB_OP_ATTN_FWD_QP:
     case OOMB_OP_ATTN_BWD_QP: {
       if (top_k < 0) return 0;
@@ -445,6 +449,26 @@ oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage
   p.page_table = page_table;
   hipError_t e = launch_offload_writeback(p, slot_pages, head_mask, n_slots, stage_capacity, const_cast<void*>(stage_dk),
                                           const_cast<void*>(stage_dv), hk, hv, (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
+oomb_status oomb_check_inputs(const oomb_attn_desc* desc, const int32_t* page_table, const int32_t* sel_pages,
+                              const int32_t* sel_count, int32_t sel_stride, int32_t lists_per_head, int32_t* violations,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!page_table || !violations) return OOMB_ERR_INVALID_ARG;
+  if (sel_pages) {
+    if (!sel_count || sel_stride < 1 || (lists_per_head != 1 && lists_per_head != p.m)) return OOMB_ERR_INVALID_ARG;
+  } else {
+    lists_per_head = 0;
+  }
+  if (!workspace || workspace_bytes < up256((size_t)desc->num_phys_pages * sizeof(int32_t))) return OOMB_ERR_WORKSPACE;
+  p.page_table = page_table;
+  p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
+  hipError_t e = launch_check_inputs(p, desc->num_phys_pages, lists_per_head, (int32_t*)workspace, violations,
+                                     (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

@@ -172,3 +172,15 @@ def test_offload_entry_points_validate_before_launch():
                                     None) == api.ERR_INVALID_ARG
     assert l.oomb_offload_writeback(ctypes.byref(d), fake, fake, None, fake, fake, fake, fake, fake, 640,
                                     None) == api.ERR_INVALID_ARG
+
+
+def test_check_inputs_validates_before_launch():
+    d = _good_desc()
+    l = api.lib()
+    fake = ctypes.c_void_p(0x1000)
+    need = api.workspace_bytes(d, 0, api.OP_CHECK_INPUTS)
+    assert need >= 512 * 4
+    assert l.oomb_check_inputs(ctypes.byref(d), None, None, None, 0, 0, fake, fake, need, None) == api.ERR_INVALID_ARG
+    assert l.oomb_check_inputs(ctypes.byref(d), fake, fake, None, 96, 1, fake, fake, need, None) == api.ERR_INVALID_ARG
+    assert l.oomb_check_inputs(ctypes.byref(d), fake, fake, fake, 96, 5, fake, fake, need, None) == api.ERR_INVALID_ARG
+    assert l.oomb_check_inputs(ctypes.byref(d), fake, None, None, 0, 0, fake, fake, need - 1, None) == api.ERR_WORKSPACE
