@@ -159,3 +159,23 @@ def test_qp_backward_is_deterministic():
         outs.append({k: v.clone() for k, v in r.items()})
     for k in outs[0]:
         assert torch.equal(outs[0][k], outs[1][k]), k
+
+
+# row-tile geometry: a query page is 4 G blocks of 32 rows -> ceil(4 G / 8) tiles; G = 1 (half a tile per query
+# page), 3 (one full + one half tile), 8 (four full tiles), 5 (two full + one half), a single query page (m = 1)
+@pytest.mark.parametrize("G,m", [(1, 3), (3, 2), (8, 2), (5, 3), (7, 1)])
+def test_mfma_tile_geometry_for_other_group_sizes(G, m):
+    w = Workload(f"qp_g{G}_m{m}", 2 * G, 2, 128, 128, 128 * m, 128 * (m + 9), None, "bf16", "f32", 0.0884, extra_phys=1,
+                 seed=80 + G)
+    sel, cnt = rand_qp_lists(w, 3, w.seed, popular=1)
+    qp_parity(w, sel, cnt)
+
+
+def test_votes_for_other_group_sizes():
+    """The vote kernels split a row tile between two query pages when 4 G is not a multiple of 8."""
+    from test_gpu_vote import vote_parity
+    for G, m in [(1, 4), (3, 3), (5, 2), (8, 2)]:
+        w = Workload(f"vote_g{G}_m{m}", 2 * G, 2, 128, 128, 128 * m, 128 * (m + 70), None, "bf16", "f32", 0.0884,
+                     boost_frac=0.1, seed=90 + G)
+        *_, differ = vote_parity(w, 5)
+        assert differ == 0, (G, m, differ)
