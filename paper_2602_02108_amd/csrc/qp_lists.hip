@@ -14,7 +14,10 @@
 namespace oomb {
 
 constexpr int QP_THREADS = 1024;
-constexpr int QP_SLICE = 8;  // query pages per dK/dV work unit
+#ifndef OOMB_QP_SLICE
+#define OOMB_QP_SLICE 8
+#endif
+constexpr int QP_SLICE = OOMB_QP_SLICE;  // query pages per dK/dV work unit (at most 64: they are held in one register)
 
 struct QpLayout {
   int32_t un_cap, max_units, max_pslots, max_multi;
@@ -30,8 +33,8 @@ QpLayout qp_layout(const Params& p, int32_t stride) {
   const int64_t entries = (int64_t)p.m * stride;
   L.un_cap = (int32_t)(entries < p.n ? entries : p.n);
   L.max_units = (int32_t)(L.un_cap + entries / QP_SLICE + 1);
-  // a page held by c > QP_SLICE lists is cut into ceil(c / QP_SLICE) < c / 4 units
-  L.max_pslots = (int32_t)(entries / 4 + 1);
+  // a page held by c > QP_SLICE lists is cut into ceil(c / QP_SLICE) < 2 c / QP_SLICE units
+  L.max_pslots = (int32_t)(2 * entries / QP_SLICE + 1);
   L.max_multi = (int32_t)(entries / (QP_SLICE + 1) + 1);  // such a page is held by more than QP_SLICE lists
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += up256(bytes); return at; };
