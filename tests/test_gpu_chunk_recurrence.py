@@ -1,0 +1,82 @@
+"""Several chunks in sequence, as the training loop drives the path (paper Sec. 3: chunk-recurrent training,
+Eq. 2-3; Sec. 4.1: the KV cache grows chunk by chunk, KV gradients of earlier chunks accumulate over later
+chunks): append chunk t's K / V (page means cached at append time), retrieve, attend, back-propagate into
+the persistent gradient pools.  The GPU sequence is compared with the oracle running the same sequence;
+lists are compared chunk by chunk, the pools at the end."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_02108_amd import api
+from paper_2602_02108_amd.workloads import Workload, to_numpy, torch_dtype
+
+import oracle as orc
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("votes", [False, True], ids=["pooled", "votes"])
+def test_three_chunks_in_sequence(votes):
+    Hq, Hkv, D, P, C, chunks, top_k = 14, 2, 128, 128, 256, 3, 3
+    hist0 = 6                      # pages already in the cache before the first chunk
+    m = C // P
+    n_final = hist0 + chunks * m
+    n_phys = n_final + 2
+    gen = torch.Generator().manual_seed(20260301)
+    dt = torch.bfloat16
+    k_pool = torch.randn((n_phys, Hkv, P, D), generator=gen).to(dt).cuda()
+    v_pool = torch.randn((n_phys, Hkv, P, D), generator=gen).to(dt).cuda()
+    page_table = torch.randperm(n_phys, generator=gen).to(torch.int32).cuda()
+    dk_pool = torch.zeros((n_phys, Hkv, P, D), dtype=torch.float32, device="cuda")
+    dv_pool = torch.zeros_like(dk_pool)
+    cache = torch.zeros((n_final, Hkv, D), dtype=torch.float32, device="cuda")
+    sm_scale = 0.0884
+
+    # oracle state (host copies of the same bits)
+    ok, ov, opt = to_numpy(k_pool), to_numpy(v_pool), to_numpy(page_table)
+    odk = np.zeros(dk_pool.shape, np.float32)
+    odv = np.zeros(dk_pool.shape, np.float32)
+    ocache = np.zeros(cache.shape, np.float32)
+
+    # the history that precedes the first chunk: its means enter the cache
+    w0 = Workload("hist", Hq, Hkv, D, P, C, (hist0 + m) * P, top_k, "bf16", "f32", sm_scale)
+    desc0 = api.make_desc(torch.empty((C, Hq, D), dtype=dt, device="cuda"), k_pool, w0.N, sm_scale, torch.float32)
+    api.page_means(desc0, k_pool, page_table, 0, hist0, cache)
+    ocache = orc.page_means(pu.shape_of(w0), ok, opt, 0, hist0, ocache)
+
+    for t in range(chunks):
+        N = (hist0 + (t + 1) * m) * P
+        w = Workload(f"chunk{t}", Hq, Hkv, D, P, C, N, top_k, "bf16", "f32", sm_scale)
+        sh = pu.shape_of(w)
+        q = torch.randn((C, Hq, D), generator=gen).to(dt).cuda()
+        d_o = torch.randn((C, Hq, D), generator=gen).to(dt).cuda()
+        kc = torch.randn((C, Hkv, D), generator=gen).to(dt).cuda()
+        vc = torch.randn((C, Hkv, D), generator=gen).to(dt).cuda()
+        desc = api.make_desc(q, k_pool, N, sm_scale, torch.float32)
+        hq, hdo = to_numpy(q), to_numpy(d_o)
+
+        api.kv_append(desc, kc, vc, page_table, k_pool, v_pool, cache)
+        ok, ov, ocache = orc.kv_append(sh, to_numpy(kc), to_numpy(vc), opt, ok, ov, ocache)
+        if votes:
+            sel, cnt = api.page_vote_topk(desc, q, cache, top_k)
+            o, lse = api.paged_attn_fwd_qp(desc, q, k_pool, v_pool, page_table, sel, cnt)
+            api.paged_attn_bwd_qp(desc, q, k_pool, v_pool, page_table, o, lse, d_o, dk_pool, dv_pool, sel, cnt)
+            osel, ocnt, _ = orc.page_vote_topk(sh, hq, ocache, top_k)
+        else:
+            sel, cnt = api.page_score_topk_cached(desc, q, cache, top_k)
+            o, lse = api.paged_attn_fwd(desc, q, k_pool, v_pool, page_table, sel, cnt)
+            api.paged_attn_bwd(desc, q, k_pool, v_pool, page_table, o, lse, d_o, dk_pool, dv_pool, sel, cnt)
+            osel, ocnt, _ = orc.page_score_topk_cached(sh, hq, ocache, top_k)
+        torch.cuda.synchronize()
+        assert np.array_equal(cache.cpu().numpy().view(np.uint32), ocache.view(np.uint32)), f"chunk {t}: cached means"
+        assert np.array_equal(sel.cpu().numpy(), osel) and np.array_equal(cnt.cpu().numpy(), ocnt), f"chunk {t}: lists"
+        ref = orc.attn_fwd_bwd(sh, hq, ok, ov, opt, hdo, osel, ocnt, dk_pool=odk, dv_pool=odv, prec="f32")
+        pu.check(f"O (chunk {t})", pu.f32(o), ref["o"], "bf16")
+        odk, odv = ref["dk_pool"], ref["dv_pool"]
+
+    assert np.array_equal(to_numpy(k_pool).view(np.uint16), ok.view(np.uint16))
+    pu.check("dK pool after all chunks", pu.f32(dk_pool), odk, "bf16")
+    pu.check("dV pool after all chunks", pu.f32(dv_pool), odv, "bf16")
+    # pages of later chunks received no gradient from earlier ones, early pages received several contributions
+    assert dk_pool[page_table[:hist0].long()].abs().sum() > 0
