@@ -413,11 +413,15 @@ def main():
     # measured ceilings of this device (outside the timed region): an MFMA issue loop and a streaming copy
     cbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     ceil_mfma = api.calibrate(0, cbuf)
+    ceil_mfma_random = api.calibrate(2, cbuf)   # same loop on random operands: the clock follows the switching activity
     ceil_copy = api.calibrate(1, cbuf)
     del cbuf
     props = torch.cuda.get_device_properties(0)
     roof["measured_ceiling"] = ceil_mfma if roof["bound"] == "mfma" else ceil_copy
     roof["frac_of_measured_ceiling"] = roof["achieved"] / roof["measured_ceiling"]
+    if roof["bound"] == "mfma":
+        roof["measured_ceiling_random_operands"] = ceil_mfma_random
+        roof["frac_of_measured_ceiling_random_operands"] = roof["achieved"] / ceil_mfma_random
     # per phase: algorithmic FLOPs over the summed kernel times of the phase
     def phase_ms(names):
         return sum(kernels[k]["avg_ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
@@ -453,9 +457,11 @@ def main():
         "ms_per_step_runs": repeats_ms, "ms_per_step_min": min(repeats_ms), "ms_per_chunk": per_chunk_ms,
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "max_clock_mhz": rocminfo_max_clock_mhz()},
-        "ceilings": {"mfma_bf16_tflops_measured": ceil_mfma, "copy_gbs_measured": ceil_copy,
+        "ceilings": {"mfma_bf16_tflops_measured": ceil_mfma, "mfma_bf16_tflops_measured_random_operands": ceil_mfma_random,
+                     "copy_gbs_measured": ceil_copy,
                      "mfma_bf16_tflops_peak": MFMA_BF16_PEAK_TFLOPS, "hbm_gbs_peak": HBM_PEAK_GBS,
-                     "value_frac_of_measured_mfma": flops / dt / 1e12 / ceil_mfma},
+                     "value_frac_of_measured_mfma": flops / dt / 1e12 / ceil_mfma,
+                     "value_frac_of_measured_mfma_random_operands": flops / dt / 1e12 / ceil_mfma_random},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -329,7 +329,12 @@ int32_t oomb_profile_read(int32_t idx, char* name, int32_t name_cap, double* tot
  * Benchmark aid (not part of the paper's method): a measured ceiling of the device,
  * to set kernel rates against something other than the data-sheet peaks.
  *   which = 0: every SIMD issues independent 32x32x16 bf16 matrix instructions back
- *              to back; *result = TFLOP/s.  buf is only a sink (>= 4096 bytes).
+ *              to back on constant operands; *result = TFLOP/s.  buf is only a sink
+ *              (>= 4096 bytes).
+ *   which = 2: the same instruction stream on operands with random signs and mantissas
+ *              that change from one instruction to the next (the clock of the part
+ *              follows the switching activity of the matrix units, so this is the
+ *              ceiling of a kernel that multiplies real data); *result = TFLOP/s.
  *   which = 1: a streaming kernel copies the first half of buf (device memory,
  *              16-byte aligned, `bytes` long) to its second half; *result = GB/s
  *              counting bytes read + bytes written.

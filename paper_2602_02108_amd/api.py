@@ -358,7 +358,8 @@ def profile_read() -> dict:
 
 
 def calibrate(which: int, buf) -> float:
-    """oomb_calibrate: measured ceiling of the device (0: bf16 MFMA TFLOP/s, 1: copy GB/s, read + write)."""
+    """oomb_calibrate: measured ceiling of the device (0: bf16 MFMA TFLOP/s on constant operands, 2: on random
+    operands, 1: copy GB/s, read + write)."""
     out = ctypes.c_double()
     st = lib().oomb_calibrate(int(which), _p(buf), buf.numel() * buf.element_size(), ctypes.byref(out), _stream(buf))
     if st != OK:
