@@ -50,7 +50,8 @@ typedef enum {
   OOMB_ERR_INVALID_ARG = 1, /* NULL pointer, non-divisible sizes, bad stride/alignment */
   OOMB_ERR_UNSUPPORTED = 2, /* shape / dtype combination with no kernel */
   OOMB_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than oomb_workspace_bytes() */
-  OOMB_ERR_LAUNCH = 4       /* HIP reported a launch error */
+  OOMB_ERR_LAUNCH = 4,      /* HIP reported a launch error */
+  OOMB_ERR_OUT_OF_PAGES = 5 /* oomb_page_pool_alloc: fewer free pages than asked for */
 } oomb_status;
 
 typedef enum { OOMB_F32 = 0, OOMB_BF16 = 1 } oomb_dtype;
@@ -242,6 +243,29 @@ oomb_status oomb_page_score_topk_cached(const oomb_attn_desc* desc, const void* 
                                         void* hip_stream);
 oomb_status oomb_local_page_list(const oomb_attn_desc* desc, int32_t window_pages, int32_t* sel_pages,
                                  int32_t* sel_count, void* hip_stream);
+
+/*
+ * Page bookkeeping of the paged memory manager (Sec. 4.1: the KV cache and its gradients
+ * live in fixed-size pages handed out on demand, so a growing context never reallocates
+ * or fragments memory).  The K, V, dK and dV pools share one page numbering, so one
+ * free list serves all four.  HOST-side and stateless: the caller owns
+ *     free_stack [num_phys_pages] int32, host   the free physical pages (a stack)
+ *     n_free     int64, host                    how many of its leading entries are valid
+ * and builds the page table from the pages it is given (entries n_past .. n-1 of
+ * `page_table` for oomb_kv_append).  Deterministic: after a reset pages come out in
+ * ascending order 0, 1, 2, ...; released pages are reused last-released-first.
+ *   oomb_page_pool_reset    every page free.
+ *   oomb_page_pool_alloc    pops `count` pages into pages_out[count]; if fewer are free nothing
+ *                           changes and OOMB_ERR_OUT_OF_PAGES is returned (the pools are full).
+ *   oomb_page_pool_release  pushes pages[count] back (in the order given).  A page out of range, listed
+ *                           twice or already free: OOMB_ERR_INVALID_ARG, nothing changes
+ *                           (checked against the whole stack: O(count * n_free)).
+ * NULL pointers and negative counts: OOMB_ERR_INVALID_ARG.  No device work, no stream.
+ */
+oomb_status oomb_page_pool_reset(int64_t num_phys_pages, int32_t* free_stack, int64_t* n_free);
+oomb_status oomb_page_pool_alloc(int32_t* free_stack, int64_t* n_free, int64_t count, int32_t* pages_out);
+oomb_status oomb_page_pool_release(int64_t num_phys_pages, int32_t* free_stack, int64_t* n_free,
+                                   const int32_t* pages, int64_t count);
 
 /*
  * Offloaded KV cache (Sec. 4.3: the KV cache and its gradients are kept in host memory, the

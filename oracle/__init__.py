@@ -430,3 +430,33 @@ def check_inputs(sh: Shape, n_phys: int, page_table, sel=None, sel_count=None) -
         if not set(need) <= set(int(v) for v in e):
             bad |= CHECK_LIST_LOCAL
     return bad
+
+
+class PagePool:
+    """Free list of the physical pages shared by the K / V / dK / dV pools (paper Sec. 4.1: pages are handed
+    out on demand as the context grows, so nothing is reallocated).  A plain Python list used as a stack:
+    after a reset pages come out in ascending order; released pages are reused last-released-first.
+    `alloc` raises MemoryError when fewer than `count` pages are free (state unchanged), `release` raises
+    ValueError for a page that is out of range, listed twice or already free (state unchanged)."""
+
+    def __init__(self, num_phys_pages: int):
+        self.num_phys_pages = int(num_phys_pages)
+        self.free = list(range(self.num_phys_pages - 1, -1, -1))   # top of the stack = end of the list
+
+    @property
+    def n_free(self) -> int:
+        return len(self.free)
+
+    def alloc(self, count: int) -> list:
+        if count < 0:
+            raise ValueError("negative count")
+        if count > len(self.free):
+            raise MemoryError("page pool exhausted")
+        return [self.free.pop() for _ in range(count)]
+
+    def release(self, pages) -> None:
+        pages = [int(x) for x in pages]
+        if len(set(pages)) != len(pages) or any(x < 0 or x >= self.num_phys_pages for x in pages) or \
+                set(pages) & set(self.free):
+            raise ValueError("bad page in release")
+        self.free.extend(pages)

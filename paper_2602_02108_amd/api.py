@@ -12,7 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liboomb.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = range(5)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH, ERR_OUT_OF_PAGES = range(6)
 F32, BF16 = 0, 1
 OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD, OP_VOTE_TOPK, OP_ATTN_FWD_QP, OP_ATTN_BWD_QP, \
     OP_CHECK_INPUTS = range(7)
@@ -21,6 +21,7 @@ EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd"
            "oomb_paged_attn_bwd", "oomb_status_string", "oomb_version", "oomb_profile_enable",
            "oomb_profile_reset", "oomb_profile_count", "oomb_profile_read", "oomb_calibrate",
            "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
+           "oomb_page_pool_reset", "oomb_page_pool_alloc", "oomb_page_pool_release",
            "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk",
            "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback", "oomb_check_inputs"]
 
@@ -97,6 +98,12 @@ def lib():
         l.oomb_page_score_topk_cached.argtypes = [dp, vp, fp, i32, vp, vp, vp, vp, u64, vp]
         l.oomb_local_page_list.restype = i32
         l.oomb_local_page_list.argtypes = [dp, i32, vp, vp, vp]
+        l.oomb_page_pool_reset.restype = i32
+        l.oomb_page_pool_reset.argtypes = [i64, vp, ctypes.POINTER(i64)]
+        l.oomb_page_pool_alloc.restype = i32
+        l.oomb_page_pool_alloc.argtypes = [vp, ctypes.POINTER(i64), i64, vp]
+        l.oomb_page_pool_release.restype = i32
+        l.oomb_page_pool_release.argtypes = [i64, vp, ctypes.POINTER(i64), vp, i64]
         l.oomb_calibrate.restype = i32
         l.oomb_calibrate.argtypes = [i32, vp, u64, ctypes.POINTER(ctypes.c_double), vp]
         _lib = l
@@ -373,6 +380,37 @@ def kv_append(desc: AttnDesc, k_chunk, v_chunk, page_table, k_pool, v_pool, kbar
                               _p(kbar_cache), _stream(k_pool))
     if st != OK:
         raise OombError(st, "oomb_kv_append")
+
+
+class PagePool:
+    """Free list of the physical pages that the K / V / dK / dV pools share (oomb_page_pool_*): host-side state
+    (a stack of page ids and its fill level) held here, every operation done by the library."""
+
+    def __init__(self, num_phys_pages: int):
+        self.num_phys_pages = int(num_phys_pages)
+        self._stack = (ctypes.c_int32 * max(self.num_phys_pages, 1))()
+        self._n_free = ctypes.c_int64(0)
+        st = lib().oomb_page_pool_reset(self.num_phys_pages, self._stack, ctypes.byref(self._n_free))
+        if st != OK:
+            raise OombError(st, "oomb_page_pool_reset")
+
+    @property
+    def n_free(self) -> int:
+        return int(self._n_free.value)
+
+    def alloc(self, count: int) -> list:
+        out = (ctypes.c_int32 * max(int(count), 1))()
+        st = lib().oomb_page_pool_alloc(self._stack, ctypes.byref(self._n_free), int(count), out)
+        if st != OK:
+            raise OombError(st, "oomb_page_pool_alloc")
+        return list(out[: int(count)])
+
+    def release(self, pages) -> None:
+        pages = [int(x) for x in pages]
+        arr = (ctypes.c_int32 * max(len(pages), 1))(*pages)
+        st = lib().oomb_page_pool_release(self.num_phys_pages, self._stack, ctypes.byref(self._n_free), arr, len(pages))
+        if st != OK:
+            raise OombError(st, "oomb_page_pool_release")
 
 
 def page_means(desc: AttnDesc, k_pool, page_table, first_page: int, n_pages: int, kbar_cache) -> None:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "liboomb.so")
-SOURCES = ["api.hip", "score_topk.hip", "vote_topk.hip", "kv_manager.hip", "offload.hip", "check.hip", "attn_generic.hip", "kv_layout.hip", "qp_lists.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "attn_bwd_dkv_mfma.hip", "profile.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "score_topk.hip", "vote_topk.hip", "kv_manager.hip", "page_pool.hip", "offload.hip", "check.hip", "attn_generic.hip", "kv_layout.hip", "qp_lists.hip", "attn_fwd_mfma.hip", "attn_bwd_mfma.hip", "attn_bwd_dkv_mfma.hip", "profile.hip", "calibrate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

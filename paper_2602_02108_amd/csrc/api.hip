@@ -479,6 +479,7 @@ const char* oomb_status_string(int32_t status) {
     case OOMB_ERR_UNSUPPORTED: return "unsupported shape or dtype";
     case OOMB_ERR_WORKSPACE: return "workspace missing or too small";
     case OOMB_ERR_LAUNCH: return "kernel launch failed";
+    case OOMB_ERR_OUT_OF_PAGES: return "page pool exhausted";
     default: return "unknown status";
   }
 }

@@ -27,7 +27,18 @@ def test_three_chunks_in_sequence(votes):
     dt = torch.bfloat16
     k_pool = torch.randn((n_phys, Hkv, P, D), generator=gen).to(dt).cuda()
     v_pool = torch.randn((n_phys, Hkv, P, D), generator=gen).to(dt).cuda()
-    page_table = torch.randperm(n_phys, generator=gen).to(torch.int32).cuda()
+    # pages come from the manager's free list, scrambled by an earlier "sequence" that held every page
+    # and gave them back in a seeded order; the history takes its pages now, every chunk takes m more
+    pool, opool = api.PagePool(n_phys), orc.PagePool(n_phys)
+    order = torch.randperm(n_phys, generator=gen).tolist()
+    for pl in (pool, opool):
+        pl.alloc(n_phys)
+        pl.release(order)
+    pages = pool.alloc(hist0)
+    assert pages == opool.alloc(hist0)
+    page_table = torch.zeros(n_final, dtype=torch.int32)
+    page_table[:hist0] = torch.tensor(pages, dtype=torch.int32)
+    page_table = page_table.cuda()
     dk_pool = torch.zeros((n_phys, Hkv, P, D), dtype=torch.float32, device="cuda")
     dv_pool = torch.zeros_like(dk_pool)
     cache = torch.zeros((n_final, Hkv, D), dtype=torch.float32, device="cuda")
@@ -55,6 +66,10 @@ def test_three_chunks_in_sequence(votes):
         vc = torch.randn((C, Hkv, D), generator=gen).to(dt).cuda()
         desc = api.make_desc(q, k_pool, N, sm_scale, torch.float32)
         hq, hdo = to_numpy(q), to_numpy(d_o)
+        new_pages = pool.alloc(m)
+        assert new_pages == opool.alloc(m)
+        page_table[N // P - m: N // P] = torch.tensor(new_pages, dtype=torch.int32, device="cuda")
+        opt = to_numpy(page_table)
 
         api.kv_append(desc, kc, vc, page_table, k_pool, v_pool, cache)
         ok, ov, ocache = orc.kv_append(sh, to_numpy(kc), to_numpy(vc), opt, ok, ov, ocache)
@@ -80,3 +95,4 @@ def test_three_chunks_in_sequence(votes):
     pu.check("dV pool after all chunks", pu.f32(dv_pool), odv, "bf16")
     # pages of later chunks received no gradient from earlier ones, early pages received several contributions
     assert dk_pool[page_table[:hist0].long()].abs().sum() > 0
+    assert pool.n_free == opool.n_free == n_phys - n_final and len(set(page_table.tolist())) == n_final
