@@ -151,3 +151,64 @@ def test_stress_4m_history():
     _check_rows(w, hx, res, osel, ocnt, _sample_rows(w, 64, 3))
     _check_identities(w, x, res)
     _untouched(w, x, res, osel, ocnt, hx["page_table"])
+
+
+def test_benchmark_sequence_of_16_chunks():
+    """The sequence bench.py times: 16 calls with the history growing by one chunk per call (1M -> 1M + 15 C),
+    workspaces and outputs allocated once for the longest history, gradient pools persisting across the
+    calls.  Checked: the last (longest) call against the oracle -- selection in full, sampled rows -- and the
+    pools after all 16 calls through the identities <dV, V> = sum over calls <dO, O> and <dK, K> = sum <dQ, Q>,
+    which hold for the accumulated gradients."""
+    w = WORKLOADS["qwen_sparse_1m"]
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    dev = x["q"].device
+    steps = w.extra_phys // w.m + 1
+    assert steps == 16
+    gdt = torch_dtype(w.grad_dtype)
+    descs = [api.make_desc(x["q"], x["k_pool"], w.N + s * w.C, w.sm_scale, gdt) for s in range(steps)]
+    ws = {op: torch.empty(api.workspace_bytes(descs[-1], w.top_k, op), dtype=torch.uint8, device=dev)
+          for op in (api.OP_SCORE_TOPK, api.OP_ATTN_FWD, api.OP_ATTN_BWD)}
+    sel = torch.empty((w.Hkv, w.top_k + w.m), dtype=torch.int32, device=dev)
+    cnt = torch.empty((w.Hkv,), dtype=torch.int32, device=dev)
+    o = torch.empty_like(x["q"])
+    lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(x["q"])
+    rhs_v = torch.zeros(w.Hkv, dtype=torch.float64, device=dev)
+    rhs_k = torch.zeros(w.Hkv, dtype=torch.float64, device=dev)
+    mass_v = torch.zeros(w.Hkv, dtype=torch.float64, device=dev)
+    mass_k = torch.zeros(w.Hkv, dtype=torch.float64, device=dev)
+    touched = [set() for _ in range(w.Hkv)]
+    for s, desc in enumerate(descs):
+        api.page_score_topk(desc, x["q"], x["k_pool"], x["page_table"], w.top_k, sel, cnt, workspace=ws[api.OP_SCORE_TOPK])
+        api.paged_attn_fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse, ws[api.OP_ATTN_FWD])
+        api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"],
+                           x["dv_pool"], sel, cnt, dq, ws[api.OP_ATTN_BWD])
+        for g in range(w.Hkv):
+            hs = slice(g * w.G, (g + 1) * w.G)
+            rhs_v[g] += (x["d_o"][:, hs].double() * o[:, hs].double()).sum()
+            rhs_k[g] += (dq[:, hs].double() * x["q"][:, hs].double()).sum()
+            mass_v[g] += (x["d_o"][:, hs].double().abs() * o[:, hs].double().abs()).sum()
+            mass_k[g] += (dq[:, hs].double().abs() * x["q"][:, hs].double().abs()).sum()
+        hsel, hcnt = sel.cpu().numpy(), cnt.cpu().numpy()
+        for g in range(w.Hkv):
+            touched[g] |= set(hsel[g][:hcnt[g]].tolist())
+    torch.cuda.synchronize()
+
+    # the last call against the oracle
+    last = w.with_(name="qwen_sparse_1m_last", N=w.N + (steps - 1) * w.C, extra_phys=0)
+    assert last.n == w.n_phys
+    osel, ocnt, _ = pu.oracle_select(last, hx)
+    assert np.array_equal(hcnt, ocnt) and np.array_equal(hsel, osel)
+    res = dict(o=o, lse=lse, dq=dq)
+    _check_rows(last, hx, res, osel, ocnt, _sample_rows(last, 64, 4))
+
+    # the pools after the 16 calls
+    for g in range(w.Hkv):
+        lhs_v = (x["dv_pool"][:, g].double() * x["v_pool"][:, g].double()).sum().item()
+        lhs_k = (x["dk_pool"][:, g].double() * x["k_pool"][:, g].double()).sum().item()
+        assert abs(lhs_v - rhs_v[g].item()) <= 5e-3 * mass_v[g].item(), (g, lhs_v, rhs_v[g].item())
+        assert abs(lhs_k - rhs_k[g].item()) <= 5e-3 * mass_k[g].item(), (g, lhs_k, rhs_k[g].item())
+        untouched = np.setdiff1d(np.arange(w.n_phys), hx["page_table"][np.array(sorted(touched[g]))])
+        idx = torch.as_tensor(untouched, device=dev)
+        assert not x["dk_pool"][idx, g].any() and not x["dv_pool"][idx, g].any()

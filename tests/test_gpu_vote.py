@@ -257,3 +257,82 @@ def test_votes_path_4m_stress():
                      for i in (0, 31, 32, w.P - 1, int(rng.integers(w.P)), int(rng.integers(w.P)))], dtype=np.int32)
     full._check_rows(w, hx, res, osel, ocnt, rows)
     full._check_identities(w, x, res)
+
+
+def test_benchmark_sequence_of_16_chunks_with_votes():
+    """The sequence bench.py --retrieval votes --cached-means times: 16 calls with the history growing by one
+    chunk per call, page means cached once, workspaces and outputs allocated for the longest history, gradient
+    pools persisting.  Checked: lists of two query pages of one KV head in the last call against the oracle,
+    rows of those query pages, and the pools after all 16 calls through <dV, V> = sum over calls <dO, O> and
+    <dK, K> = sum <dQ, Q>; pages in no list of any call are untouched."""
+    import test_gpu_parity_full as full
+    w = WORKLOADS["qwen_sparse_1m"]
+    top_k, g0, taus = w.top_k, 3, [5, w.m - 1]
+    x = make_inputs(w, "cuda")
+    hx = pu.host_inputs(x)
+    dev = x["q"].device
+    steps = w.extra_phys // w.m + 1
+    gdt = torch_dtype(w.grad_dtype)
+    descs = [api.make_desc(x["q"], x["k_pool"], w.N + s * w.C, w.sm_scale, gdt) for s in range(steps)]
+    ws = {op: torch.empty(api.workspace_bytes(descs[-1], top_k, op), dtype=torch.uint8, device=dev)
+          for op in (api.OP_VOTE_TOPK, api.OP_ATTN_FWD_QP, api.OP_ATTN_BWD_QP)}
+    sel = torch.empty((w.Hkv, w.m, top_k + w.m), dtype=torch.int32, device=dev)
+    cnt = torch.empty((w.Hkv, w.m), dtype=torch.int32, device=dev)
+    votes = torch.zeros((w.Hkv, w.m, w.n_phys - w.m), dtype=torch.float32, device=dev)
+    o = torch.empty_like(x["q"])
+    lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(x["q"])
+    cache = torch.zeros((w.n_phys, w.Hkv, w.D), dtype=torch.float32, device=dev)
+    api.page_means(descs[-1], x["k_pool"], x["page_table"], 0, w.n_phys, cache)
+    acc = torch.zeros((4, w.Hkv), dtype=torch.float64, device=dev)   # rhs_v, rhs_k, mass_v, mass_k
+    touched = [set() for _ in range(w.Hkv)]
+    for s, desc in enumerate(descs):
+        last = s == steps - 1
+        api.page_vote_topk(desc, x["q"], cache, top_k, sel, cnt, votes_out=votes if last else None,
+                           workspace=ws[api.OP_VOTE_TOPK])
+        api.paged_attn_fwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse,
+                              ws[api.OP_ATTN_FWD_QP])
+        api.paged_attn_bwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"],
+                              x["dv_pool"], sel, cnt, dq, ws[api.OP_ATTN_BWD_QP])
+        for g in range(w.Hkv):
+            hs = slice(g * w.G, (g + 1) * w.G)
+            acc[0, g] += (x["d_o"][:, hs].double() * o[:, hs].double()).sum()
+            acc[1, g] += (dq[:, hs].double() * x["q"][:, hs].double()).sum()
+            acc[2, g] += (x["d_o"][:, hs].double().abs() * o[:, hs].double().abs()).sum()
+            acc[3, g] += (dq[:, hs].double().abs() * x["q"][:, hs].double().abs()).sum()
+        hsel = sel.cpu().numpy()
+        for g in range(w.Hkv):
+            touched[g] |= set(hsel[g][hsel[g] >= 0].tolist())
+    torch.cuda.synchronize()
+    hcnt = cnt.cpu().numpy()
+
+    # the last call: two query pages of head g0 against the oracle
+    lw = w.with_(name="qwen_sparse_1m_last", N=w.N + (steps - 1) * w.C, extra_phys=0)
+    okb = orc.page_means(pu.shape_of(lw), hx["k_pool"], hx["page_table"], 0, lw.n_past,
+                         np.zeros((lw.n, lw.Hkv, lw.D), np.float32))
+    assert np.array_equal(cache[: lw.n_past].cpu().numpy().view(np.uint32), okb[: lw.n_past].view(np.uint32))
+    osel_g, ocnt_g, ovotes_g = _oracle_lists_of_head(lw, hx, okb, g0, top_k, taus)
+    hv = votes[g0, :, : lw.n_past].cpu().numpy()
+    osel = np.full((lw.Hkv, lw.m, top_k + lw.m), -1, np.int32)
+    ocnt = np.zeros((lw.Hkv, lw.m), np.int32)
+    for tau in taus:
+        err = np.abs(hv[tau] - ovotes_g[tau]) / np.maximum(ovotes_g[tau], 1e-30)
+        assert err.max() < VOTE_RTOL, (tau, err.max())
+        assert hcnt[g0, tau] == ocnt_g[tau]
+        assert np.array_equal(hsel[g0, tau], osel_g[tau]), f"list of query page {tau} differs from the oracle's"
+        osel[g0, tau], ocnt[g0, tau] = osel_g[tau], ocnt_g[tau]
+    rng = np.random.default_rng(6)
+    rows = np.array([(g0 * w.G + int(rng.integers(w.G)), tau * w.P + int(i)) for tau in taus
+                     for i in (0, 31, 32, w.P - 1, int(rng.integers(w.P)), int(rng.integers(w.P)))], dtype=np.int32)
+    full._check_rows(lw, hx, dict(o=o, lse=lse, dq=dq), osel, ocnt, rows)
+
+    # the pools after the 16 calls
+    acc = acc.cpu().numpy()
+    for g in range(w.Hkv):
+        lhs_v = (x["dv_pool"][:, g].double() * x["v_pool"][:, g].double()).sum().item()
+        lhs_k = (x["dk_pool"][:, g].double() * x["k_pool"][:, g].double()).sum().item()
+        assert abs(lhs_v - acc[0, g]) <= 5e-3 * acc[2, g], (g, lhs_v, acc[0, g])
+        assert abs(lhs_k - acc[1, g]) <= 5e-3 * acc[3, g], (g, lhs_k, acc[1, g])
+        untouched = np.setdiff1d(np.arange(w.n_phys), hx["page_table"][np.array(sorted(touched[g]))])
+        idx = torch.as_tensor(untouched, device=dev)
+        assert not x["dk_pool"][idx, g].any() and not x["dv_pool"][idx, g].any()
