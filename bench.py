@@ -407,6 +407,14 @@ def main():
             f = line.split()
             if len(f) == 5 and f[0] == name and f[1] == "read_bytes" and f[3] == "write_bytes":
                 roof["traffic"] = int(f[2]) + int(f[4])
+    # matrix-pipe utilisation of the dominant kernel by hardware counters (busy cycles of the matrix pipes over
+    # 4 SIMDs x busy cycles of the compute units), from the committed SQ counter profile of this workload
+    upath = os.path.join(ROOT, "profiles", f"mfma_utilisation_{w.name}.txt")
+    if roof["bound"] == "mfma" and os.path.exists(upath):
+        for line in open(upath):
+            f = line.split()
+            if len(f) == 7 and f[0] == name and f[5] == "utilisation":
+                roof["mfma_utilisation_by_counters"] = float(f[6])
     kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof_all.items()}
     for k, v in prof.items():  # the large kernels: durations of the timed region itself
         kernels[k] = {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]}
