@@ -4,41 +4,7 @@
 #include <cstdlib>
 
 #include "common.h"
-
-namespace oomb {
-size_t score_workspace_bytes(const Params& p);
-hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel, int32_t* sel_count,
-                             float* scores_out, void* ws, const float* kbar_cache, hipStream_t st);
-hipError_t launch_kv_append(const Params& p, bool is_bf16, const void* kc, const void* vc, void* k_pool, void* v_pool,
-                            float* cache, hipStream_t st);
-hipError_t launch_page_means(const Params& p, bool is_bf16, int64_t first, int64_t count, float* cache, hipStream_t st);
-hipError_t launch_local_page_list(const Params& p, int32_t window, int32_t* sel, int32_t* sel_count, hipStream_t st);
-hipError_t launch_delta(const Params& p, bool is_bf16, hipStream_t st);
-hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st);
-hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
-bool mfma_supported(const Params& p, bool is_bf16);
-hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
-size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
-hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
-size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
-size_t vote_workspace_bytes(const Params& p, bool is_bf16, bool force_generic);
-hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const float* kbar, int32_t top_k, int32_t* sel,
-                            int32_t* sel_count, float* votes_out, void* ws, hipStream_t st);
-void* device_view(const void* ptr);
-hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
-                               uint32_t* head_mask, int32_t* n_slots, hipStream_t st);
-hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* slot_pages, const uint32_t* head_mask,
-                                const int32_t* n_slots, int32_t stage_cap, void* host_k, void* host_v, void* stage_k,
-                                void* stage_v, void* stage_dk, void* stage_dv, hipStream_t st);
-hipError_t launch_offload_writeback(const Params& p, const int32_t* slot_pages, const uint32_t* head_mask,
-                                    const int32_t* n_slots, int32_t stage_cap, void* stage_dk, void* stage_dv, void* host_dk,
-                                    void* host_dv, hipStream_t st);
-hipError_t launch_check_inputs(const Params& p, int64_t num_phys, int32_t lists_per_head, int32_t* marks, int32_t* out,
-                               hipStream_t st);
-size_t qp_maps_bytes(const Params& p, int32_t stride);
-int32_t qp_union_cap(const Params& p, int32_t stride);
-hipError_t launch_qp_prepare(Params& p, void* ws, hipStream_t st);
-}  // namespace oomb
+#include "launch.h"
 
 using namespace oomb;
 

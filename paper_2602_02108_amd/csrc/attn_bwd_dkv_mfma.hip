@@ -26,6 +26,7 @@
 // the next 64 KiB, so that every operand address is a loop-invariant register plus
 // an immediate; the loops are unrolled by two stages to make the stage a constant.
 #include "mfma_common.h"
+#include "launch.h"
 
 namespace oomb {
 
@@ -453,8 +454,6 @@ __global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(Params p, const flo
   TG* pool = (TG*)(which == 0 ? p.dk_pool : p.dv_pool) + pool_off;
   kv_rmw4<TG>(pool, s.x, s.y, s.z, s.w);
 }
-
-int32_t qp_max_pslots(const Params& p, int32_t stride);
 
 size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split) {
   if (p.qp) return (size_t)p.Hkv * (size_t)qp_max_pslots(p, p.sel_stride) * 2 * TP * HD * sizeof(float);

@@ -13,6 +13,7 @@
 //                dQ^T += K^T dS^T.  Every lane owns one query row.
 //   bwd_dkv    : (attn_bwd_dkv_mfma.hip) one workgroup OWNS one (KV head, selected page).
 #include "mfma_common.h"
+#include "launch.h"
 
 namespace oomb {
 
@@ -351,19 +352,12 @@ __global__ __launch_bounds__(256) void bwd_layout_kernel(Params p, const float* 
   }
 }
 
-size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split);
-int32_t dkv_splits(const Params& p, int32_t max_len);
-hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
-                               float* partial_ws, hipStream_t st);
-
 static inline size_t stats_bytes(const Params& p) {
   return (2 * (size_t)p.Hkv * (size_t)rows_padded(p) * sizeof(float) + 255) & ~(size_t)255;
 }
 static inline int32_t img_stages(const Params& p) { return (p.C / 32) * p.G / 2; }
 static inline size_t img_bytes(const Params& p) { return (size_t)p.Hkv * (size_t)img_stages(p) * IMG_STRIDE; }
 
-size_t kv_image_bytes(const Params& p, int32_t max_len, int kinds);
-hipError_t launch_kv_layout(const Params& p, int32_t max_len, int kinds, void* img, hipStream_t st);
 constexpr int DQ_IMG_KINDS = 1 | 2 | 4;  // K natural, V natural, K transposed
 
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {

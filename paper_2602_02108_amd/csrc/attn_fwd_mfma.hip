@@ -23,6 +23,7 @@
 // (Sec. 4.2, votes per query page) -- the list of the tile's query page, whose
 // entries name their K/V images by position in the union of the head's lists.
 #include "mfma_common.h"
+#include "launch.h"
 
 namespace oomb {
 
@@ -320,8 +321,6 @@ bool mfma_supported(const Params& p, bool is_bf16) {
   return is_bf16 && p.D == HD && p.P == TP;
 }
 
-size_t kv_image_bytes(const Params& p, int32_t max_len, int kinds);
-hipError_t launch_kv_layout(const Params& p, int32_t max_len, int kinds, void* img, hipStream_t st);
 constexpr int FW_IMG_KINDS = 1 | 8;  // K natural, V transposed
 
 size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {

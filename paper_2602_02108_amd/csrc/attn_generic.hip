@@ -4,6 +4,7 @@
 // dK/dV pool is updated without atomics.  Forward: Sec. 4.1 operator; backward:
 // Sec. 3 Eq. 3 accumulation into the paged gradient pool.
 #include "common.h"
+#include "launch.h"
 
 namespace oomb {
 

@@ -3,6 +3,7 @@
 // hold retrieved pages plus the chunk's own pages).  The hot path trusts them; this kernel reads
 // the same arrays, never dereferences an unchecked index, and reports a bit mask of violations.
 #include "common.h"
+#include "launch.h"
 
 namespace oomb {
 

@@ -11,6 +11,7 @@
 // half tile ht is keys 64 (ht % 2) .. + 63 of list entry ht / 2 and the kinds are the
 // set bits of `kinds` in the order K natural, V natural, K transposed, V transposed.
 #include "mfma_common.h"
+#include "launch.h"
 
 namespace oomb {
 

@@ -8,6 +8,7 @@
 // The means and scores use the fixed fp32 operation order of the streaming scorer
 // (score_topk.hip), so both paths give the same bits.
 #include "common.h"
+#include "launch.h"
 #include "rowsum.h"
 
 #pragma clang fp contract(off)

@@ -21,6 +21,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "launch.h"
 
 namespace oomb {
 

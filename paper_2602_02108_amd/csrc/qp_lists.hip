@@ -10,6 +10,7 @@
 //     into several units gets partial-sum slots, added to the pool in a fixed order.
 // One workgroup per KV head; its phases are separated by workgroup barriers.
 #include "common.h"
+#include "launch.h"
 
 namespace oomb {
 

@@ -7,6 +7,7 @@
 //   dot product as a stride-halving tree over d.  No fused multiply-add.
 // The page-mean kernel is HBM-bound: it streams every past key once.
 #include "common.h"
+#include "launch.h"
 #include "rowsum.h"
 
 #pragma clang fp contract(off)
@@ -196,8 +197,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
   for (int32_t j = k_eff + n_loc + tid; j < stride; j += SELECT_THREADS) out[j] = -1;
   if (tid == 0) sel_count[g] = k_eff + n_loc;
 }
-
-hipError_t launch_page_score_cached(const Params& p, const float* qbar, const float* cache, float* scores, hipStream_t st);
 
 static hipError_t launch_topk_select(const Params& p, const float* scores, int32_t top_k, int32_t* sel, int32_t* sel_count,
                                      int per_qp, hipStream_t st) {

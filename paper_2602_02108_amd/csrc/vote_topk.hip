@@ -16,6 +16,7 @@
 // selection kernel runs once per (KV head, query page).  No atomics: bit-reproducible.
 // Shapes without a matrix kernel (fp32 tensors, D or P != 128) take two plain kernels.
 #include "mfma_common.h"
+#include "launch.h"
 
 namespace oomb {
 
@@ -260,9 +261,6 @@ __global__ __launch_bounds__(256) void vote_sum_generic_kernel(Params p, const f
 }
 
 // ---- host side ----------------------------------------------------------------------------------
-bool mfma_supported(const Params& p, bool is_bf16);
-hipError_t launch_topk_select_qp(const Params& p, const float* votes, int32_t top_k, int32_t* sel, int32_t* sel_count,
-                                 hipStream_t st);
 
 struct VoteLayout {
   int32_t n_ht, tpq;
