@@ -15,10 +15,11 @@
 //   role 1 ("dS"): dP = dO V^T (+ bias), one block later dS = P o dP,
 //                  dK^T += Q^T dS.           Holds the V rows and dK^T.
 // In the (query x key) accumulator layout a lane owns one key column and 16 query
-// rows, so the per-row statistics would differ per register.  They are folded into
-// the matrix product instead: one extra MFMA adds -LSE/c (resp. -Delta) to every
-// column of a row, from a per-lane (row) value split into two bf16 terms (prepared once,
-// together with the swizzled Q / dO tile images, by a layout kernel).
+// rows, so the per-row statistics differ per register.  They are folded into the matrix
+// product: the accumulator chain of a block does not start from zero but from -LSE/c
+// (resp. -Delta) of the register's row, read from the stage's bias words (fp32, prepared
+// once, together with the swizzled Q / dO tile images, by a layout kernel) straight into
+// the accumulator registers.
 //
 // LDS: two stages of 64 query rows x {Q natural, dO natural, Q transposed, dO
 // transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) + bias words = 145 KiB.  The
@@ -119,7 +120,6 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) kvf[kk] = as_bf16x8(*reinterpret_cast<const uint4*>(base + 16 * kk + 8 * hh));
   }
-  const bf16x8 ones = as_bf16x8(make_uint4(0x3f803f80u, 0u, 0u, 0u));
 
   // stages (2 blocks = 64 rows) this unit visits: from the first token block that can see
   // the page, cut into n_split slices
@@ -192,13 +192,15 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   auto copy_transposed = [&](const int32_t s, const int st) __attribute__((always_inline)) {
     copy_kib_to_lds<4>(img_g + (int64_t)s * IMG_STRIDE + 32768, cp_off, KV_TR + st * 32768 + 4096 * wave);
   };
-  // this role's bias word of this lane's row of block `half` of stage buffer st
-  const uint32_t bias_o = KV_BIAS + (role * 64 + lq) * 4;
-  auto load_bias = [&](const int st, const int half) __attribute__((always_inline)) -> uint32_t {
-    return *reinterpret_cast<const uint32_t*>(smem + (bias_o + (st * 512 + half * 128)));
-  };
-  auto bias_of = [&](const uint32_t w) __attribute__((always_inline)) -> bf16x8 {
-    return as_bf16x8(make_uint4(hh == 0 ? w : 0u, 0u, 0u, 0u));
+  // this role's bias words of block `half` of stage buffer st, as the initial value of a (query x key)
+  // accumulator: register x belongs to row 8 (x / 4) + 4 hh + x % 4 of the block
+  const uint32_t bias_o = KV_BIAS + (role * 64 + 4 * hh) * 4;
+  auto load_bias = [&](const int st, const int half, f32x16& chain) __attribute__((always_inline)) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const float4 v = *reinterpret_cast<const float4*>(smem + (bias_o + (st * 512 + half * 128 + a * 32)));
+      chain[4 * a + 0] = v.x; chain[4 * a + 1] = v.y; chain[4 * a + 2] = v.z; chain[4 * a + 3] = v.w;
+    }
   };
   // barrier between the two steps of a stage: the transposed half of this stage (issued one stage
   // ago) must have landed; the natural half of the next stage (4 loads, 5 for waves 0 and 1) may
@@ -253,11 +255,9 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
   auto frag = [&](const int idx) __attribute__((always_inline)) -> bf16x8 { return __builtin_bit_cast(bf16x8, fr[idx]); };
   // batches 0 and 1 must already be on their way into fr[0..3] and fr[4..7]; three sets rotate, two
   // batches are in flight while one computes
-  auto matrix_phase = [&](const int st, const int half, const int natw, const int trw, const uint32_t bias_w, f32x16& chain,
+  // `chain` enters holding the bias words of its rows (load_bias, issued before the fragment fetches)
+  auto matrix_phase = [&](const int st, const int half, const int natw, const int trw, f32x16& chain,
                           const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
-#pragma unroll
-    for (int x = 0; x < 16; ++x) chain[x] = 0.f;
-    chain = mfma32(bias_of(bias_w), ones, chain);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int set = 4 * (j % 3), db = 2 * (j & 1);
@@ -305,12 +305,13 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
     if (role == 0) {
       // matrix: S = Q K^T - LSE / c  ||  dV^T += dO^T P(previous block);  vector: P = exp2(c S), masked, -> partner
       uint4 p0 = make_uint4(0, 0, 0, 0), p1 = p0;
-      auto step0 = [&](const int st, const int half, const int32_t blk, const uint32_t bias_w) __attribute__((always_inline)) {
+      auto step0 = [&](const int st, const int half, const int32_t blk) __attribute__((always_inline)) {
         f32x16 sc;
+        load_bias(st, half, sc);
         // (no fetch ahead of the barrier: the transposed tiles of this stage may still be on their way)
         fetch(st, half, 0, 1, 0, 0);
         fetch(st, half, 0, 1, 1, 4);
-        matrix_phase(st, half, 0, 1, bias_w, sc, p0, p1);
+        matrix_phase(st, half, 0, 1, sc, p0, p1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
@@ -330,11 +331,10 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         const bool more = s + 1 < s1;
         const int32_t rn = real_next(rs);
         if (more) copy_natural(rn, st ^ 1);
-        const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
-        step0(st, 0, 2 * rs, st_a);
+        step0(st, 0, 2 * rs);
         mid_barrier(more);
         if (more) copy_transposed(rn, st ^ 1);
-        step0(st, 1, 2 * rs + 1, st_b);
+        step0(st, 1, 2 * rs + 1);
         end_barrier();
         rs = rn;
       };
@@ -345,8 +345,9 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       flush_phase(1, p0, p1);
     } else {
       // vector: dS = P o dP of the previous block;  matrix: dP = dO V^T - Delta  ||  dK^T += Q^T dS(previous block)
-      auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur, const uint32_t bias_w) __attribute__((always_inline)) {
+      auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur) __attribute__((always_inline)) {
         const int ph = half ^ 1;
+        load_bias(st, half, dcur);
         const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + ph * 2048));
         const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (ph * 2048 + 1024)));
         fetch(st, half, 1, 0, 0, 0);
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         }
         const uint4 s0v = kv_pack8(dprev, 0), s1v = kv_pack8(dprev, 8);
         __builtin_amdgcn_sched_barrier(0);
-        matrix_phase(st, half, 1, 0, bias_w, dcur, s0v, s1v);
+        matrix_phase(st, half, 1, 0, dcur, s0v, s1v);
       };
       f32x16 dpa, dpb;  // dP of even / odd blocks
 #pragma unroll
@@ -370,11 +371,10 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         const bool more = s + 1 < s1;
         const int32_t rn = real_next(rs);
         if (more) copy_natural(rn, st ^ 1);
-        const uint32_t st_a = load_bias(st, 0), st_b = load_bias(st, 1);
-        step1(st, 0, dpb, dpa, st_a);
+        step1(st, 0, dpb, dpa);
         mid_barrier(more);
         if (more) copy_transposed(rn, st ^ 1);
-        step1(st, 1, dpa, dpb, st_b);
+        step1(st, 1, dpa, dpb);
         end_barrier();
         rs = rn;
       };

@@ -303,9 +303,8 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
 //   [32K, 48K) Q  transposed: row = dim d, granule o = 2u + hh holds rows 16u + 4hh + {0..3, 8..11};
 //                             at (d * 8 + (o ^ ((d >> 1) & 7))) * 16
 //   [48K, 64K) dO transposed
-// followed by one 256-byte record of bias words per stage: word [which][row], the per-row
-// statistic (-LSE / c for which = 0, -Delta for which = 1) split into bf16 high and low
-// parts, ready to be used as the first two contraction slots of an MFMA A operand.
+// followed by the bias words of the stage: float [which][row], the per-row statistic (-LSE / c for
+// which = 0, -Delta for which = 1) from which the dK/dV kernel starts its accumulator chains.
 constexpr int IMG_BYTES = 65536;
 constexpr int IMG_STRIDE = IMG_BYTES + 512;
 
@@ -346,9 +345,7 @@ __global__ __launch_bounds__(256) void bwd_layout_kernel(Params p, const float* 
     const float c = p.sm_scale * 1.4426950408889634f;
     const int64_t ri = (int64_t)g * rows_pad + (int64_t)64 * s + tid;
     const float v = which == 0 ? -lse2_rs[ri] / c : -delta_rs[ri];
-    const uint32_t hi = pack2_bf16(v, 0.f) & 0xffffu;
-    const uint32_t lo = pack2_bf16(v - __uint_as_float(hi << 16), 0.f) & 0xffffu;
-    reinterpret_cast<uint32_t*>(out + IMG_BYTES)[which * 64 + tid] = hi | (lo << 16);
+    reinterpret_cast<float*>(out + IMG_BYTES)[which * 64 + tid] = v;
   }
 }
 
