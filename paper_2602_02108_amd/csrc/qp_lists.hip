@@ -7,7 +7,9 @@
 //   * for every list entry its position in that union (where its image sits);
 //   * for every union page the query pages whose list holds it (inverse lists, CSR,
 //     ascending), cut into dK/dV work units of at most QP_SLICE query pages; a page cut
-//     into several units gets partial-sum slots, added to the pool in a fixed order.
+//     into several units gets partial-sum slots, added to the pool in a fixed order.  The
+//     unit table is ordered by the first query page of the units (in windows of QP_SLICE),
+//     so that workgroups running at the same time walk rows of neighbouring query pages.
 // One workgroup per KV head; its phases are separated by workgroup barriers.
 #include "common.h"
 #include "launch.h"
@@ -179,25 +181,42 @@ __global__ __launch_bounds__(QP_THREADS) void qp_prepare_kernel(Params p, int32_
     my_slots += ns > 1 ? ns : 0;
     my_multi += ns > 1;
   }
-  int32_t n_units, n_slots, n_multi;
-  int32_t k_at = block_exclusive_scan(my_units, wave_tot, n_units);
+  int32_t n_units_all, n_slots, n_multi;
+  (void)block_exclusive_scan(my_units, wave_tot, n_units_all);
   int32_t s_at = block_exclusive_scan(my_slots, wave_tot, n_slots);
   int32_t m_at = block_exclusive_scan(my_multi, wave_tot, n_multi);
   for (int32_t u = u0; u < u1; ++u) {
     const int32_t c = invoff[u + 1] - invoff[u];
     const int32_t ns = (c + QP_SLICE - 1) / QP_SLICE;
-    const int32_t base = ns > 1 ? g * max_pslots + s_at : -1;
-    pbase[u] = base;
+    pbase[u] = ns > 1 ? g * max_pslots + s_at : -1;
     ns_out[u] = ns;
-    for (int32_t s = 0; s < ns; ++s) {
-      const int32_t q0 = s * QP_SLICE, qc = c - q0 < QP_SLICE ? c - q0 : QP_SLICE;
-      units[k_at + s] = make_int4(u, q0, qc, ns > 1 ? base + s : -1);
-    }
-    k_at += ns;
     if (ns > 1) {
       s_at += ns;
       multi[m_at++] = u;
     }
+  }
+  // the unit table, ordered by the window (QP_SLICE consecutive query pages) that holds a unit's first
+  // query page, then by page: workgroups that run at the same time start on rows of the same few query
+  // pages.  One scan per window.
+  int32_t n_units = 0;
+  const int32_t windows = (m + QP_SLICE - 1) / QP_SLICE;
+  for (int32_t win = 0; win < windows; ++win) {
+    int32_t mine = 0;
+    for (int32_t u = u0; u < u1; ++u) {
+      const int32_t c = invoff[u + 1] - invoff[u];
+      for (int32_t q0 = 0; q0 < c; q0 += QP_SLICE) mine += invqp[invoff[u] + q0] / QP_SLICE == win;
+    }
+    int32_t total;
+    int32_t k_at = n_units + block_exclusive_scan(mine, wave_tot, total);
+    for (int32_t u = u0; u < u1; ++u) {
+      const int32_t c = invoff[u + 1] - invoff[u];
+      for (int32_t q0 = 0, sl = 0; q0 < c; q0 += QP_SLICE, ++sl) {
+        if (invqp[invoff[u] + q0] / QP_SLICE != win) continue;
+        const int32_t qc = c - q0 < QP_SLICE ? c - q0 : QP_SLICE;
+        units[k_at++] = make_int4(u, q0, qc, pbase[u] >= 0 ? pbase[u] + sl : -1);
+      }
+    }
+    n_units += total;
   }
   if (tid == 0) {
     ucnt[g] = n_units;
