@@ -60,3 +60,59 @@ def test_captured_step_replays_like_the_eager_step(name):
         got = snapshot()
         for a, b in zip(got, want):
             assert torch.equal(a, b), f"replay {r} differs from the eager step"
+
+
+def test_captured_votes_step_replays_like_the_eager_step():
+    """The per-query-page path (votes, list maps built on the device, attention over one list per query page)
+    under capture: same check as above."""
+    w = WORKLOADS["mid_sparse_bf16"]
+    top_k = w.top_k
+    x = make_inputs(w, "cuda")
+    desc = api.make_desc(x["q"], x["k_pool"], w.N, w.sm_scale, torch_dtype(w.grad_dtype))
+    dev = x["q"].device
+    ws = {op: torch.empty(api.workspace_bytes(desc, top_k, op), dtype=torch.uint8, device=dev)
+          for op in (api.OP_VOTE_TOPK, api.OP_ATTN_FWD_QP, api.OP_ATTN_BWD_QP)}
+    cache = torch.zeros((w.n, w.Hkv, w.D), dtype=torch.float32, device=dev)
+    sel = torch.empty((w.Hkv, w.m, top_k + w.m), dtype=torch.int32, device=dev)
+    cnt = torch.empty((w.Hkv, w.m), dtype=torch.int32, device=dev)
+    o = torch.empty_like(x["q"])
+    lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(x["q"])
+
+    def step():
+        api.page_means(desc, x["k_pool"], x["page_table"], 0, w.n_past, cache)
+        api.page_vote_topk(desc, x["q"], cache, top_k, sel, cnt, workspace=ws[api.OP_VOTE_TOPK])
+        api.paged_attn_fwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sel, cnt, o, lse,
+                              ws[api.OP_ATTN_FWD_QP])
+        api.paged_attn_bwd_qp(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"],
+                              x["dv_pool"], sel, cnt, dq, ws[api.OP_ATTN_BWD_QP])
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (sel, cnt, o, lse, dq, x["dk_pool"], x["dv_pool"])]
+
+    step()
+    want = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for t in (x["dk_pool"], x["dv_pool"]):
+            t.zero_()
+        step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        for t in (sel, cnt, o, lse, dq, cache):
+            t.zero_()
+        x["dk_pool"].zero_()
+        x["dv_pool"].zero_()
+        for buf in ws.values():           # the maps and partial sums of the last replay must not matter
+            buf.fill_(0x5a)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {r} differs from the eager step"
