@@ -218,7 +218,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=16,
+                    help="untimed steps before the timed ones (default: one pass over the 16-chunk sequence, after which\n"
+                         "the step time is steady; with 4 the first timed chunks still run 3 %% slower)")
     ap.add_argument("--workload", default="qwen_sparse_1m")
     ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
