@@ -2,6 +2,8 @@
 binding, run the CPU oracle on the same seeded inputs, compare."""
 from __future__ import annotations
 
+import contextlib
+
 import numpy as np
 import torch
 
@@ -12,6 +14,28 @@ from paper_2602_02108_amd.workloads import Workload, make_inputs, to_numpy, torc
 
 # tolerances (the benchmark spec): bf16 tensors max-abs 2e-2 and rel-L2 5e-3; fp32 runs rel-L2 1e-4
 TOL = {"bf16": dict(max_abs=2e-2, rel_l2=5e-3), "f32": dict(max_abs=1e-3, rel_l2=1e-4)}
+
+
+MFMA_KERNELS = ("attn_fwd_mfma", "bwd_dq_mfma", "bwd_dkv_mfma")
+
+
+@contextlib.contextmanager
+def kernels_ran(names=MFMA_KERNELS, absent=("attn_fwd_generic", "attn_bwd_generic", "delta")):
+    """Asserts that the library launched every kernel in `names` (and none in `absent`) inside the block:
+    a bf16 test that silently ran the generic fp32 kernels would still pass its tolerances."""
+    api.profile_reset()
+    api.profile_enable(1)
+    try:
+        yield
+        torch.cuda.synchronize()
+        seen = api.profile_read()
+    finally:
+        api.profile_enable(0)
+        api.profile_reset()
+    for k in names:
+        assert k in seen and seen[k][1] > 0, f"kernel {k} did not run; launched: {sorted(seen)}"
+    for k in absent:
+        assert k not in seen, f"kernel {k} ran; launched: {sorted(seen)}"
 
 
 def shape_of(w: Workload) -> Shape:
