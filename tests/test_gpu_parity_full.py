@@ -101,15 +101,19 @@ def _unit_pages(w, osel, ocnt, g):
     return past + local
 
 
+def _check_pages(w, hx, res, osel, ocnt, g, pages):
+    """dK / dV of the given logical pages of KV head g, element by element."""
+    dk = np.zeros(hx["k_pool"].shape, dtype=np.float32)
+    dv = np.zeros(hx["k_pool"].shape, dtype=np.float32)
+    _oracle_units(w, hx, osel, ocnt, g, pages, dk, dv)
+    _compare_units(hx, res, g, pages, dk, dv)
+
+
 def _check_units(w, hx, res, osel, ocnt, heads):
     """dK / dV of sampled (KV head, page) units, element by element.  The KV heads of a call run on different
     XCD pairs of the device, so more than one is sampled."""
     for g in heads:
-        pages = _unit_pages(w, osel, ocnt, g)
-        dk = np.zeros(hx["k_pool"].shape, dtype=np.float32)
-        dv = np.zeros(hx["k_pool"].shape, dtype=np.float32)
-        _oracle_units(w, hx, osel, ocnt, g, pages, dk, dv)
-        _compare_units(hx, res, g, pages, dk, dv)
+        _check_pages(w, hx, res, osel, ocnt, g, _unit_pages(w, osel, ocnt, g))
 
 
 def _check_identities(w, x, res):

@@ -206,7 +206,7 @@ def test_votes_path_full_size():
     full._check_rows(w, hx, res, osel, ocnt, rows)
     held = np.bincount(osel_g[osel_g >= 0], minlength=w.n)          # lists that hold each page
     pages = [int(union[0]), int(np.argmax(held[: w.n_past])), int(w.n_past), int(w.n_past + w.m // 2), int(w.n - 1)]
-    full._check_units(w, hx, res, osel, ocnt, g0, sorted(set(pages)))
+    full._check_pages(w, hx, res, osel, ocnt, g0, sorted(set(pages)))
     full._check_identities(w, x, res)
     # pages in no list of head g0 are untouched
     untouched = np.setdiff1d(np.arange(w.n_phys), hx["page_table"][union])
