@@ -51,7 +51,8 @@ typedef enum {
   OOMB_ERR_UNSUPPORTED = 2, /* shape / dtype combination with no kernel */
   OOMB_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than oomb_workspace_bytes() */
   OOMB_ERR_LAUNCH = 4,      /* HIP reported a launch error */
-  OOMB_ERR_OUT_OF_PAGES = 5 /* oomb_page_pool_alloc: fewer free pages than asked for */
+  OOMB_ERR_OUT_OF_PAGES = 5, /* oomb_page_pool_alloc: fewer free pages than asked for */
+  OOMB_ERR_SCRATCH_LIMIT = 6 /* oomb_page_score_topk_noalloc: the shape needs more than the built-in scratch */
 } oomb_status;
 
 typedef enum { OOMB_F32 = 0, OOMB_BF16 = 1 } oomb_dtype;
@@ -116,6 +117,25 @@ oomb_status oomb_page_score_topk(const oomb_attn_desc* desc, const void* q, cons
                                  const int32_t* page_table, int32_t top_k, int32_t* sel_pages,
                                  int32_t* sel_count, float* scores_out, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
+
+/*
+ * oomb_page_score_topk for callers that cannot allocate or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace, same kernels, same results bit for bit; the scoring scratch (query-page sums, pooled
+ * queries and, when scores_out is NULL, the scores) lives in a static device array of
+ * OOMB_NOALLOC_SCRATCH_BYTES that every device the library runs on holds until the process ends.
+ * Nothing is allocated or freed, here or in any library the call reaches (the first call on a device
+ * looks the array's address up once).  A shape whose oomb_workspace_bytes(desc, top_k,
+ * OOMB_OP_SCORE_TOPK) exceeds OOMB_NOALLOC_SCRATCH_BYTES is refused with OOMB_ERR_SCRATCH_LIMIT before
+ * anything is launched (Hq * m * D + Hkv * (D + n_past) floats: the 4M-token benchmark shape needs
+ * 1.4 MiB).  All calls on one device share the one array, which keeps the last call's contents (no
+ * part of it has to start at zero): calls that overlap on a device -- two streams, two threads --
+ * race; serialise them.
+ */
+#define OOMB_NOALLOC_SCRATCH_BYTES (4u << 20)
+oomb_status oomb_page_score_topk_noalloc(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                         const int32_t* page_table, int32_t top_k, int32_t* sel_pages,
+                                         int32_t* sel_count, float* scores_out, void* hip_stream);
 
 /*
  * Paged attention forward (Sec. 4.1 operator over the pages of Sec. 4.2).

@@ -12,7 +12,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liboomb.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH, ERR_OUT_OF_PAGES = range(6)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH, ERR_OUT_OF_PAGES, ERR_SCRATCH_LIMIT = range(7)
+NOALLOC_SCRATCH_BYTES = 4 << 20
 F32, BF16 = 0, 1
 OP_SCORE_TOPK, OP_ATTN_FWD, OP_ATTN_BWD, OP_VOTE_TOPK, OP_ATTN_FWD_QP, OP_ATTN_BWD_QP, \
     OP_CHECK_INPUTS = range(7)
@@ -23,7 +24,8 @@ EXPORTS = ["oomb_workspace_bytes", "oomb_page_score_topk", "oomb_paged_attn_fwd"
            "oomb_kv_append", "oomb_page_means", "oomb_page_score_topk_cached", "oomb_local_page_list",
            "oomb_page_pool_reset", "oomb_page_pool_alloc", "oomb_page_pool_release",
            "oomb_paged_attn_fwd_qp", "oomb_paged_attn_bwd_qp", "oomb_page_vote_topk",
-           "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback", "oomb_check_inputs"]
+           "oomb_offload_plan", "oomb_offload_fetch", "oomb_offload_writeback", "oomb_check_inputs",
+           "oomb_page_score_topk_noalloc"]
 
 
 class AttnDesc(ctypes.Structure):
@@ -61,6 +63,8 @@ def lib():
         l.oomb_workspace_bytes.argtypes = [dp, i32, i32]
         l.oomb_page_score_topk.restype = i32
         l.oomb_page_score_topk.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
+        l.oomb_page_score_topk_noalloc.restype = i32
+        l.oomb_page_score_topk_noalloc.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp]
         l.oomb_paged_attn_fwd.restype = i32
         l.oomb_paged_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, u64, vp]
         l.oomb_paged_attn_bwd.restype = i32
@@ -173,6 +177,15 @@ def page_score_topk(desc: AttnDesc, q, k_pool, page_table, top_k: int, sel_pages
                                     _stream(q))
     if st != OK:
         raise OombError(st, "oomb_page_score_topk")
+    return sel_pages, sel_count
+
+
+def page_score_topk_noalloc(desc: AttnDesc, q, k_pool, page_table, top_k: int, sel_pages, sel_count, scores_out=None):
+    """oomb_page_score_topk_noalloc: every buffer is the caller's; nothing is allocated here either."""
+    st = lib().oomb_page_score_topk_noalloc(ctypes.byref(desc), _p(q), _p(k_pool), _p(page_table), int(top_k),
+                                            _p(sel_pages), _p(sel_count), _p(scores_out), _stream(q))
+    if st != OK:
+        raise OombError(st, "oomb_page_score_topk_noalloc")
     return sel_pages, sel_count
 
 

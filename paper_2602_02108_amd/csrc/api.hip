@@ -147,6 +147,24 @@ oomb_status oomb_page_score_topk(const oomb_attn_desc* desc, const void* q, cons
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 
+oomb_status oomb_page_score_topk_noalloc(const oomb_attn_desc* desc, const void* q, const void* k_pool,
+                                         const int32_t* page_table, int32_t top_k, int32_t* sel_pages,
+                                         int32_t* sel_count, float* scores_out, void* hip_stream) {
+  Params p{};
+  oomb_status s = check_desc(desc, &p);
+  if (s != OOMB_OK) return s;
+  if (!q || !k_pool || !page_table || !sel_pages || !sel_count || top_k < 0) return OOMB_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_pool)) return OOMB_ERR_INVALID_ARG;
+  if (p.n_past > (1 << 20)) return OOMB_ERR_UNSUPPORTED;
+  if (score_workspace_bytes(p) > (size_t)OOMB_NOALLOC_SCRATCH_BYTES) return OOMB_ERR_SCRATCH_LIMIT;
+  void* ws = nullptr;
+  if (score_scratch_ptr(&ws) != hipSuccess) return OOMB_ERR_LAUNCH;
+  p.q = q; p.k_pool = k_pool; p.page_table = page_table;
+  hipError_t e = launch_score_topk(p, desc->dtype == OOMB_BF16, top_k, sel_pages, sel_count, scores_out, ws, nullptr,
+                                   (hipStream_t)hip_stream);
+  return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
+}
+
 oomb_status oomb_page_score_topk_cached(const oomb_attn_desc* desc, const void* q, const float* kbar_cache,
                                         int32_t top_k, int32_t* sel_pages, int32_t* sel_count, float* scores_out,
                                         void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -446,6 +464,7 @@ const char* oomb_status_string(int32_t status) {
     case OOMB_ERR_WORKSPACE: return "workspace missing or too small";
     case OOMB_ERR_LAUNCH: return "kernel launch failed";
     case OOMB_ERR_OUT_OF_PAGES: return "page pool exhausted";
+    case OOMB_ERR_SCRATCH_LIMIT: return "shape exceeds the built-in scratch buffer";
     default: return "unknown status";
   }
 }

@@ -10,6 +10,7 @@ namespace oomb {
 size_t score_workspace_bytes(const Params& p);
 hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32_t* sel, int32_t* sel_count,
                              float* scores_out, void* ws, const float* kbar_cache, hipStream_t st);
+hipError_t score_scratch_ptr(void** out);  // this device's copy of the built-in scoring scratch array
 hipError_t launch_topk_select_qp(const Params& p, const float* votes, int32_t top_k, int32_t* sel, int32_t* sel_count,
                                  hipStream_t st);
 

@@ -6,6 +6,8 @@
 //   token sums left to right; qbar sums query pages (outer) then heads (inner);
 //   dot product as a stride-halving tree over d.  No fused multiply-add.
 // The page-mean kernel is HBM-bound: it streams every past key once.
+#include <mutex>
+
 #include "common.h"
 #include "launch.h"
 #include "rowsum.h"
@@ -260,6 +262,32 @@ hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32
     else launch_scoring<float, 64>(p, A, qbar, scores, kbar_cache, st);
   }
   return launch_topk_select(p, scores, top_k, sel, sel_count, 0, st);
+}
+
+// Built-in scratch memory of oomb_page_score_topk_noalloc: the scoring workspace (query-page sums, pooled
+// queries, scores) for callers that cannot hand one over.  Every device the library runs on holds its own
+// copy of the array until the process ends.  In host code the array's name is only a stand-in; the address
+// on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[OOMB_NOALLOC_SCRATCH_BYTES];
+
+hipError_t score_scratch_ptr(void** out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* ptrs[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptrs[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    ptrs[dev] = ptr;
+  }
+  *out = ptrs[dev];
+  return hipSuccess;
 }
 
 // votes [Hkv][m][n_past] -> one list per (KV head, query page), sel [Hkv][m][top_k + m]

@@ -184,3 +184,16 @@ def test_check_inputs_validates_before_launch():
     assert l.oomb_check_inputs(ctypes.byref(d), fake, fake, None, 96, 1, fake, fake, need, None) == api.ERR_INVALID_ARG
     assert l.oomb_check_inputs(ctypes.byref(d), fake, fake, fake, 96, 5, fake, fake, need, None) == api.ERR_INVALID_ARG
     assert l.oomb_check_inputs(ctypes.byref(d), fake, None, None, 0, 0, fake, fake, need - 1, None) == api.ERR_WORKSPACE
+
+
+def test_noalloc_scoring_refuses_shapes_beyond_its_scratch():
+    # Hq * m * D floats of query-page sums alone: 64 * 512 * 128 * 4 B = 16 MiB > the 4 MiB built-in array
+    d = _good_desc(n_q_heads=64, chunk_len=65536, ctx_len=131072, num_phys_pages=1024, q_tok_stride=64 * 128)
+    assert api.workspace_bytes(d, 8, api.OP_SCORE_TOPK) > api.NOALLOC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: the size check comes before any launch
+    st = api.lib().oomb_page_score_topk_noalloc(ctypes.byref(d), fake, fake, fake, 8, fake, fake, None, None)
+    assert st == api.ERR_SCRATCH_LIMIT
+    assert "scratch" in api.status_string(api.ERR_SCRATCH_LIMIT)
+    # bad arguments are still reported first
+    st = api.lib().oomb_page_score_topk_noalloc(ctypes.byref(_good_desc()), fake, None, fake, 8, fake, fake, None, None)
+    assert st == api.ERR_INVALID_ARG
