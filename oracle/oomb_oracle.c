@@ -438,7 +438,6 @@ static int64_t row_logits(const oomb_oracle_desc *d, const void *Q, const void *
       const int64_t pos = l * P + t;
       if (pos > a_i) break;
       real dot = 0;
-#pragma omp simd reduction(+ : dot)
       for (int dd = 0; dd < D; ++dd)
         dot += ld(Q, ((int64_t)i * Hq + h) * D + dd, bf) * ld(Kpool, base + (int64_t)t * D + dd, bf);
       s[nv] = scale * dot;
@@ -571,7 +570,6 @@ void oomb_oracle_attn_bwd_dq(const oomb_oracle_desc *d, const void *Q, const voi
         const int64_t base = ((int64_t)page_table[tok[j] / P] * Hkv + g) * P * D + (tok[j] % P) * D;
         const real p = R_EXP(s[j] - lse);
         real dp = 0;
-#pragma omp simd reduction(+ : dp)
         for (int dd = 0; dd < D; ++dd)
           dp += ld(dO, ((int64_t)i * Hq + h) * D + dd, bf) * ld(Vpool, base + dd, bf);
         const real ds = p * (dp - delta);
@@ -657,10 +655,8 @@ void oomb_oracle_attn_bwd_dkv(const oomb_oracle_desc *d, const void *Q, const vo
           if (!mem[n_tau > 1 ? i / P : 0]) continue; /* the row's list does not hold this page */
           const int64_t qoff = ((int64_t)i * Hq + h) * D;
           real dot = 0, dp = 0;
-#pragma omp simd reduction(+ : dot)
           for (int dd = 0; dd < D; ++dd)
             dot += ld(Q, qoff + dd, bf) * ld(Kpool, base + (int64_t)t * D + dd, bf);
-#pragma omp simd reduction(+ : dp)
           for (int dd = 0; dd < D; ++dd)
             dp += ld(dO, qoff + dd, bf) * ld(Vpool, base + (int64_t)t * D + dd, bf);
           const real p = R_EXP(scale * dot - LSE[(int64_t)h * C + i]);
