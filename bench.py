@@ -85,8 +85,7 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
     shape = (cap,) + tuple(x["k_pool"].shape[1:])
     bufs = [dict(k=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev), v=torch.empty(shape, dtype=x["k_pool"].dtype, device=dev),
                  dk=torch.empty(shape, dtype=gdt, device=dev), dv=torch.empty(shape, dtype=gdt, device=dev),
-                 sel=torch.empty_like(sel), cnt=torch.empty_like(cnt), plan=api.OffloadPlan(d_max, cap, dev),
-                 pt=torch.empty(n_max // w.P, dtype=torch.int32, device=dev))
+                 sel=torch.empty_like(sel), cnt=torch.empty_like(cnt), plan=api.OffloadPlan(d_max, cap, dev))
             for _ in range(3)]
     main = torch.cuda.current_stream()
     copy = torch.cuda.Stream()
@@ -101,8 +100,7 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
     def select_plan(s, b):
         N, desc = desc_at(s)
         select(desc, b["sel"], b["cnt"])
-        api.offload_plan(desc, b["sel"], b["cnt"], b["plan"])
-        torch.clamp(b["plan"].stage_table, min=0, out=b["pt"])
+        api.offload_plan(desc, b["sel"], b["cnt"], b["plan"])   # plan.stage_table = page table of the staging pools
 
     def fetch(s, b, stream):
         N, desc = desc_at(s)
@@ -110,8 +108,9 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
 
     def attend(s, b):
         N, desc = desc_at(s)
-        fwd(desc, x["q"], b["k"], b["v"], b["pt"], b["sel"], b["cnt"], o, lse, ws_fw)
-        bwd(desc, x["q"], b["k"], b["v"], b["pt"], o, lse, x["d_o"], b["dk"], b["dv"], b["sel"], b["cnt"], dq, ws_bw)
+        pt = b["plan"].stage_table
+        fwd(desc, x["q"], b["k"], b["v"], pt, b["sel"], b["cnt"], o, lse, ws_fw)
+        bwd(desc, x["q"], b["k"], b["v"], pt, o, lse, x["d_o"], b["dk"], b["dv"], b["sel"], b["cnt"], dq, ws_bw)
 
     def writeback(s, b, stream):
         N, desc = desc_at(s)
@@ -196,6 +195,68 @@ def offload_bench(args, w, x, api, torch, desc_at, top_k, sel, cnt, o, lse, dq, 
     }
 
 
+def quick_measure(api, torch, name, steps, warmup):
+    """One of the other benchmark configurations, outside the headline's timed region: `warmup` untimed steps, then
+    `steps` steps (streaming scorer, pooled retrieval, history fixed at the configuration's N) timed as a whole with
+    the three large attention kernels and the page scorer bracketed by events.  Returns the step time, the
+    credited TFLOP/s and the dominant kernel's roofline fraction."""
+    from paper_2602_02108_amd.workloads import WORKLOADS, make_inputs, torch_dtype
+    w = WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    x = make_inputs(w, dev)
+    desc = api.make_desc(x["q"], x["k_pool"], w.N, w.sm_scale, torch_dtype(w.grad_dtype))
+    k = w.top_k
+    lk = k if k is not None else -1
+    ws_sc = torch.empty(max(api.workspace_bytes(desc, k or 0, api.OP_SCORE_TOPK), 256), dtype=torch.uint8, device=dev)
+    ws_fw = torch.empty(api.workspace_bytes(desc, lk, api.OP_ATTN_FWD), dtype=torch.uint8, device=dev)
+    ws_bw = torch.empty(api.workspace_bytes(desc, lk, api.OP_ATTN_BWD), dtype=torch.uint8, device=dev)
+    sel = torch.empty((w.Hkv, (k or 0) + w.m), dtype=torch.int32, device=dev)
+    cnt = torch.empty((w.Hkv,), dtype=torch.int32, device=dev)
+    o, dq = torch.empty_like(x["q"]), torch.empty_like(x["q"])
+    lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
+
+    def step():
+        sl = ct = None
+        if k is not None:
+            api.page_score_topk(desc, x["q"], x["k_pool"], x["page_table"], k, sel, cnt, workspace=ws_sc)
+            sl, ct = sel, cnt
+        api.paged_attn_fwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], sl, ct, o, lse, ws_fw)
+        api.paged_attn_bwd(desc, x["q"], x["k_pool"], x["v_pool"], x["page_table"], o, lse, x["d_o"], x["dk_pool"],
+                           x["dv_pool"], sl, ct, dq, ws_bw)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    api.profile_reset()
+    api.profile_enable(2)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    api.profile_enable(False)
+    prof = api.profile_read()
+    api.profile_reset()
+    pairs = pairs_of(w, w.N)
+    flops = 14.0 * w.D * pairs * w.Hq
+    kern = {kn: v[0] / max(v[1], 1) for kn, v in prof.items()}
+    credited = {"attn_fwd_mfma": 4.0, "bwd_dq_mfma": 6.0, "bwd_dkv_mfma": 4.0}
+    dom = max(kern, key=kern.get)
+    out = {"ms_per_step": dt * 1e3 / steps, "steps": steps, "warmup": warmup, "tflops": flops * steps / dt / 1e12,
+           "frac_mfma_peak": flops * steps / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "tflop_per_step": flops / 1e12, "history_tokens": w.N, "chunk": w.C, "top_k_pages": w.top_k,
+           "grad_pool_dtype": w.grad_dtype, "kernels_ms": kern, "dominant_kernel": dom}
+    if dom in credited:
+        ach = credited[dom] * w.D * pairs * w.Hq / (kern[dom] * 1e-3) / 1e12
+        out["dominant_kernel_roofline"] = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                           "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS}
+    if "page_score" in kern:
+        gbs = w.n_past * w.P * w.D * 2 * w.Hkv / (kern["page_score"] * 1e-3) / 1e9
+        out["page_score_GBps"] = gbs
+        out["page_score_frac_hbm_peak"] = gbs / HBM_PEAK_GBS
+    return out
+
+
 def rocminfo_max_clock_mhz():
     """Max shader clock of the first GPU agent as rocminfo prints it (None if it cannot be read)."""
     try:
@@ -236,6 +297,9 @@ def main():
                          "selected pages into device staging pools and adds their gradients back (pooled retrieval, "
                          "cached page means); reports the step time without offload, with the transfers serialised, "
                          "and with the transfers on a second stream overlapping the neighbouring steps")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other benchmark configurations (dense 64K, sparse 256K, sparse 4M) "
+                         "that the default run appends as `other_workloads`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -409,6 +473,8 @@ def main():
             f = line.split()
             if len(f) == 5 and f[0] == name and f[1] == "read_bytes" and f[3] == "write_bytes":
                 roof["traffic"] = int(f[2]) + int(f[4])
+                roof["traffic_source"] = (f"profiles/hbm_traffic_{w.name}.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                                          "this command, replayed from the committed summary, not measured in this run")
     # matrix-pipe utilisation of the dominant kernel by hardware counters (busy cycles of the matrix pipes over
     # 4 SIMDs x busy cycles of the compute units), from the committed SQ counter profile of this workload
     upath = os.path.join(ROOT, "profiles", f"mfma_utilisation_{w.name}.txt")
@@ -417,6 +483,8 @@ def main():
             f = line.split()
             if len(f) == 7 and f[0] == name and f[5] == "utilisation":
                 roof["mfma_utilisation_by_counters"] = float(f[6])
+                roof["mfma_utilisation_source"] = (f"profiles/mfma_utilisation_{w.name}.txt: rocprofv3 --pmc SQ counter run of "
+                                                   "this command, replayed from the committed summary, not measured in this run")
     kernels = {k: {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]} for k, v in prof_all.items()}
     for k, v in prof.items():  # the large kernels: durations of the timed region itself
         kernels[k] = {"avg_ms": v[0] / max(v[1], 1), "launches": v[1]}
@@ -476,6 +544,20 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, args.cpu_sample_tokens)
+    plain = args.workload == "qwen_sparse_1m" and not votes and kbar_cache is None
+    if plain and not args.no_other_workloads:
+        # the other benchmark configurations, a few steps each, after the headline's buffers are gone
+        del x, ws_sc, ws_fw, ws_bw, o, dq, lse, sel, cnt
+        torch.cuda.empty_cache()
+        others = {}
+        free, _ = torch.cuda.mem_get_info()
+        for name_, steps_ in (("qwen_dense_64k", 6), ("qwen_sparse_256k", 8), ("qwen_sparse_4m", 6)):
+            if name_ == "qwen_sparse_4m" and free < 48 * 2**30:
+                others[name_] = {"skipped": "needs about 40 GiB of free device memory"}
+                continue
+            others[name_] = quick_measure(api, torch, name_, steps_, 3)
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -300,13 +300,21 @@ oomb_status oomb_page_pool_release(int64_t num_phys_pages, int32_t* free_stack, 
  * oomb_offload_plan: which pages the lists hold, and a staging slot for each.
  *     sel_pages / sel_count: lists_per_head = 1: [Hkv][sel_stride] / [Hkv] (oomb_page_score_topk*);
  *                            lists_per_head = m: [Hkv][m][sel_stride] / [Hkv][m] (oomb_page_vote_topk)
+ *     stage_capacity  pages in each staging pool (> 0)
  *     head_mask   [n] uint32 device, out: bit g set iff some list of KV head g holds the page
- *     stage_table [n] int32 device, out: slot of a held page, numbered in ascending logical page
- *                 order over all held pages; -1 otherwise
- *     slot_pages  [min(n, Hkv * lists_per_head * sel_stride)] int32 device, out: page of every slot
- *     n_slots     [1] int32 device, out
+ *     stage_table [n] int32 device, out: THE PAGE TABLE OF THE STAGING POOLS -- the slot of a held page,
+ *                 slots numbered in ascending logical page order over all held pages; -1 for a page in no
+ *                 list (the attention kernels look up listed pages only).  It never points outside the
+ *                 staging pools: a held page whose slot would be >= stage_capacity gets slot 0.
+ *     slot_pages  [stage_capacity] int32 device, out: page of every slot in use
+ *     n_slots     [2] int32 device, out: [0] slots in use = min(pages held, stage_capacity),
+ *                 [1] pages held.  n_slots[1] > stage_capacity means the staging pools are too small:
+ *                 fetch and write-back then move the first stage_capacity pages only and attention over
+ *                 the staging pools, while it stays inside them, returns meaningless values -- check
+ *                 n_slots[1] (it is device memory: with the next host synchronisation) before trusting a
+ *                 step.  min(n, Hkv * lists_per_head * sel_stride) slots always suffice.
  *   Hkv <= 32 (else OOMB_ERR_UNSUPPORTED).
- * oomb_offload_fetch: for every slot s < min(n_slots, stage_capacity), l = slot_pages[s], and every
+ * oomb_offload_fetch: for every slot s < n_slots[0] (and < stage_capacity), l = slot_pages[s], and every
  *   KV head g with bit g of head_mask[l] set,
  *     stage_k / stage_v [s][g][:][:] = host_k / host_v [page_table[l]][g][:][:]
  *   bit for bit; if stage_dk / stage_dv are given (both or neither) the same tiles of the
@@ -322,8 +330,8 @@ oomb_status oomb_page_pool_release(int64_t num_phys_pages, int32_t* free_stack, 
  * (checked with hipPointerGetAttributes before anything is launched).
  */
 oomb_status oomb_offload_plan(const oomb_attn_desc* desc, const int32_t* sel_pages, const int32_t* sel_count,
-                              int32_t sel_stride, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
-                              uint32_t* head_mask, int32_t* n_slots, void* hip_stream);
+                              int32_t sel_stride, int32_t lists_per_head, int32_t stage_capacity, int32_t* stage_table,
+                              int32_t* slot_pages, uint32_t* head_mask, int32_t* n_slots, void* hip_stream);
 oomb_status oomb_offload_fetch(const oomb_attn_desc* desc, const void* host_k_pool, const void* host_v_pool,
                                const int32_t* page_table, const int32_t* slot_pages, const uint32_t* head_mask,
                                const int32_t* n_slots, int32_t stage_capacity, void* stage_k, void* stage_v,

@@ -335,53 +335,74 @@ def attn_fwd_bwd(sh: Shape, q, k_pool, v_pool, page_table, d_o, sel=None, sel_co
 # ---------------------------------------------------------------------------------------------
 # Offloaded KV cache (Sec. 4.3: the KV cache and its gradients live in host memory; the pages a
 # chunk attends are brought to the device, the gradients of those pages are taken back).  Pure
-# data movement, written as plain loops over (KV head, list entry).
+# data movement, written as the definition over the page lists themselves:
+#   held(g)  = the logical pages in some list of KV head g
+#   union    = the pages held by any KV head, ascending
+#   slot(l)  = rank of l in union (staging pools are indexed by slot), or "overflow" when the rank is not
+#              below the staging capacity
+#   fetch:      stage[slot(l)][g]  = host[page_table[l]][g]   for every g and every l in held(g), K and V
+#   write-back: host[page_table[l]][g] += stage[slot(l)][g]   for the same (g, l), once each, dK and dV
+# Tiles of overflowing pages do not move.  sel is [Hkv][stride] (one list per KV head) or
+# [Hkv][m][stride] (one per KV head and query page), sel_count the matching [Hkv] / [Hkv][m].
 
-def offload_plan(sh: Shape, sel, sel_count):
-    """Staging slots for the pages that some list holds: slots are numbered in ascending logical page
-    order over the union of all lists.  sel is [Hkv][stride] (one list per KV head) or [Hkv][m][stride] (one
-    per KV head and query page), sel_count the matching [Hkv] / [Hkv][m].  Returns (stage_table [n] int32,
-    -1 for pages that are not staged; slot_pages [n_slots] int32, the logical page of every slot;
-    head_mask [n] uint32, bit g set iff some list of KV head g holds the page)."""
+def _held_pages(sh: Shape, sel, sel_count):
+    """held(g) for every KV head, as sorted lists of logical page ids."""
     sel = _i32(sel)
     cnt = _i32(sel_count)
-    assert sel.ndim in (2, 3) and cnt.shape == sel.shape[:-1] and sh.Hkv <= 32
-    head_mask = np.zeros(sh.n, dtype=np.uint32)
+    assert sel.ndim in (2, 3) and cnt.shape == sel.shape[:-1]
+    held = []
     for g in range(sh.Hkv):
-        lists = sel[g][None] if sel.ndim == 2 else sel[g]
-        counts = cnt[g][None] if sel.ndim == 2 else cnt[g]
+        lists = sel[g].reshape(-1, sel.shape[-1])
+        counts = cnt[g].reshape(-1)
+        pages = set()
         for lst, c in zip(lists, counts):
-            for l in lst[:c]:
-                head_mask[l] |= np.uint32(1 << g)
-    slot_pages = np.flatnonzero(head_mask).astype(np.int32)
-    stage_table = np.full(sh.n, -1, dtype=np.int32)
-    stage_table[slot_pages] = np.arange(len(slot_pages), dtype=np.int32)
-    return stage_table, slot_pages, head_mask
+            pages |= set(int(l) for l in lst[:c])
+        held.append(sorted(pages))
+    return held
 
 
-def offload_fetch(sh: Shape, host_k, host_v, page_table, slot_pages, head_mask, stage_k, stage_v):
-    """stage[s][g] = host[page_table[l]][g] for every slot s (page l = slot_pages[s]) and every KV head g
-    whose bit is set in head_mask[l] (K and V); nothing else of the staging pools is written.  Works on
-    copies, returns (stage_k, stage_v)."""
+def offload_stage_table(sh: Shape, sel, sel_count, capacity=None):
+    """The page table of the staging pools: stage_table[l] = slot(l) for the pages of the union, -1 for
+    pages in no list; a page whose slot would be >= capacity gets slot 0 (so that the table never points
+    outside the staging pools; results are then meaningless and the second return value says so).
+    Returns (stage_table [n] int32, number of pages in the union)."""
+    held = _held_pages(sh, sel, sel_count)
+    union = sorted(set().union(*held)) if held else []
+    table = np.full(sh.n, -1, dtype=np.int32)
+    for rank, l in enumerate(union):
+        table[l] = rank if capacity is None or rank < capacity else 0
+    return table, len(union)
+
+
+def offload_fetch(sh: Shape, host_k, host_v, page_table, sel, sel_count, stage_k, stage_v):
+    """Fetch step on copies of the staging pools (capacity = their page count); returns (stage_k, stage_v).
+    Nothing but the tiles (slot(l), g) with l in held(g) is written."""
     pt = _i32(page_table)
     stage_k, stage_v = stage_k.copy(), stage_v.copy()
-    for s, l in enumerate(slot_pages):
-        for g in range(sh.Hkv):
-            if (int(head_mask[l]) >> g) & 1:
+    cap = stage_k.shape[0]
+    held = _held_pages(sh, sel, sel_count)
+    union = sorted(set().union(*held))
+    for g in range(sh.Hkv):
+        for l in held[g]:
+            s = union.index(l)
+            if s < cap:
                 stage_k[s, g] = host_k[pt[l], g]
                 stage_v[s, g] = host_v[pt[l], g]
     return stage_k, stage_v
 
 
-def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_table, slot_pages, head_mask):
-    """host[page_table[l]][g] += stage[s][g] for the same (s, g) (dK and dV), in the arithmetic of the host
-    pool's dtype (float32 here; callers with bf16 pools round the sum).  Works on copies, returns
-    (host_dk, host_dv)."""
+def offload_writeback(sh: Shape, stage_dk, stage_dv, host_dk, host_dv, page_table, sel, sel_count):
+    """Write-back step on copies of the host gradient pools, in the arithmetic of their dtype (float32 here;
+    callers with bf16 pools round the sum); returns (host_dk, host_dv)."""
     pt = _i32(page_table)
     host_dk, host_dv = host_dk.copy(), host_dv.copy()
-    for s, l in enumerate(slot_pages):
-        for g in range(sh.Hkv):
-            if (int(head_mask[l]) >> g) & 1:
+    cap = stage_dk.shape[0]
+    held = _held_pages(sh, sel, sel_count)
+    union = sorted(set().union(*held))
+    for g in range(sh.Hkv):
+        for l in held[g]:
+            s = union.index(l)
+            if s < cap:
                 host_dk[pt[l], g] = host_dk[pt[l], g] + stage_dk[s, g]
                 host_dv[pt[l], g] = host_dv[pt[l], g] + stage_dv[s, g]
     return host_dk, host_dv

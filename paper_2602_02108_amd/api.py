@@ -76,7 +76,7 @@ def lib():
         l.oomb_page_vote_topk.restype = i32
         l.oomb_page_vote_topk.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, u64, vp]
         l.oomb_offload_plan.restype = i32
-        l.oomb_offload_plan.argtypes = [dp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        l.oomb_offload_plan.argtypes = [dp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
         l.oomb_offload_fetch.restype = i32
         l.oomb_offload_fetch.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         l.oomb_offload_writeback.restype = i32
@@ -140,6 +140,34 @@ def make_desc(q: torch.Tensor, k_pool: torch.Tensor, ctx_len: int, sm_scale: flo
                     k_pool.stride(0), k_pool.stride(1), k_pool.stride(2), q.stride(0), q.stride(1), n_phys)
 
 
+def _like(where: str, name: str, t: Optional[torch.Tensor], ref: torch.Tensor, dtype=None) -> None:
+    """The descriptor carries ONE stride set for Q / O / dO / dQ and one for the K / V / dK / dV pools: every tensor of
+    a family must have the shape and strides of the tensor the descriptor was made from (and the expected dtype)."""
+    if t is None:
+        return
+    want = ref.dtype if dtype is None else dtype
+    if tuple(t.shape) != tuple(ref.shape) or tuple(t.stride()) != tuple(ref.stride()) or t.dtype != want:
+        raise OombError(ERR_INVALID_ARG, f"{where}: {name} must have shape {tuple(ref.shape)}, strides {tuple(ref.stride())} "
+                                         f"and dtype {want} (got {tuple(t.shape)}, {tuple(t.stride())}, {t.dtype})")
+
+
+def _check_family(where: str, desc: "AttnDesc", q, k_pool, rows=(), pools=(), grad_pools=(), lse=None) -> None:
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (desc.n_q_heads, desc.chunk_len) or
+                            not lse.is_contiguous()):
+        raise OombError(ERR_INVALID_ARG, f"{where}: lse must be a contiguous float32 [Hq][C] tensor")
+    if (q.stride(0), q.stride(1)) != (desc.q_tok_stride, desc.q_head_stride) or _dt(q.dtype) != desc.dtype:
+        raise OombError(ERR_INVALID_ARG, f"{where}: q does not match the descriptor's strides / dtype")
+    if tuple(k_pool.stride()[:3]) != (desc.pool_page_stride, desc.pool_head_stride, desc.pool_tok_stride):
+        raise OombError(ERR_INVALID_ARG, f"{where}: k_pool does not match the descriptor's strides")
+    for name, t in rows:
+        _like(where, name, t, q)
+    for name, t in pools:
+        _like(where, name, t, k_pool)
+    gdt = torch.bfloat16 if desc.grad_dtype == BF16 else torch.float32
+    for name, t in grad_pools:
+        _like(where, name, t, k_pool, gdt)
+
+
 def _p(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -196,6 +224,7 @@ def paged_attn_fwd(desc: AttnDesc, q, k_pool, v_pool, page_table, sel_pages=None
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((desc.n_q_heads, desc.chunk_len), dtype=torch.float32, device=q.device)
+    _check_family("oomb_paged_attn_fwd", desc, q, k_pool, rows=[("o", o)], pools=[("v_pool", v_pool)], lse=lse)
     stride = 0 if sel_pages is None else int(sel_pages.stride(0))
     list_k = -1 if sel_pages is None else stride - desc.chunk_len // desc.page_size
     workspace, nbytes = _workspace(desc, list_k, OP_ATTN_FWD, q.device, workspace)
@@ -212,6 +241,8 @@ def paged_attn_bwd(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o, d
     """oomb_paged_attn_bwd.  Returns dQ; dk_pool / dv_pool are accumulated in place."""
     if d_q is None:
         d_q = torch.empty_like(q)
+    _check_family("oomb_paged_attn_bwd", desc, q, k_pool, rows=[("o", o), ("d_o", d_o), ("d_q", d_q)],
+                  pools=[("v_pool", v_pool)], grad_pools=[("dk_pool", dk_pool), ("dv_pool", dv_pool)], lse=lse)
     stride = 0 if sel_pages is None else int(sel_pages.stride(0))
     list_k = -1 if sel_pages is None else stride - desc.chunk_len // desc.page_size
     workspace, nbytes = _workspace(desc, list_k, OP_ATTN_BWD, q.device, workspace)
@@ -269,7 +300,11 @@ class OffloadPlan:
         self.stage_table = torch.empty(n, dtype=torch.int32, device=device)
         self.slot_pages = torch.empty(self.capacity, dtype=torch.int32, device=device)
         self.head_mask = torch.empty(n, dtype=torch.int32, device=device)   # bit patterns of uint32
-        self.n_slots = torch.empty(1, dtype=torch.int32, device=device)
+        self.n_slots = torch.empty(2, dtype=torch.int32, device=device)   # [slots in use, pages held]
+
+    def overflowed(self) -> bool:
+        """True iff the lists held more pages than the staging pools have slots (synchronises)."""
+        return int(self.n_slots[1].item()) > self.capacity
 
 
 def offload_capacity(desc: AttnDesc, sel_pages) -> int:
@@ -279,13 +314,14 @@ def offload_capacity(desc: AttnDesc, sel_pages) -> int:
 
 
 def offload_plan(desc: AttnDesc, sel_pages, sel_count, plan: "OffloadPlan" = None, stream=None) -> "OffloadPlan":
-    """oomb_offload_plan for lists [Hkv][stride] or [Hkv][m][stride]."""
+    """oomb_offload_plan for lists [Hkv][stride] or [Hkv][m][stride].  plan.stage_table is the page table to give
+    the attention calls that run on the staging pools; plan.capacity must be the staging pools' page count."""
     assert sel_pages.dim() in (2, 3) and sel_pages.is_contiguous() and sel_count.is_contiguous()
     lists_per_head = 1 if sel_pages.dim() == 2 else int(sel_pages.shape[1])
     if plan is None:
         plan = OffloadPlan(desc, offload_capacity(desc, sel_pages), sel_pages.device)
     st = lib().oomb_offload_plan(ctypes.byref(desc), _p(sel_pages), _p(sel_count), int(sel_pages.shape[-1]), lists_per_head,
-                                 _p(plan.stage_table), _p(plan.slot_pages), _p(plan.head_mask), _p(plan.n_slots),
+                                 plan.capacity, _p(plan.stage_table), _p(plan.slot_pages), _p(plan.head_mask), _p(plan.n_slots),
                                  _stream_of(stream, sel_pages))
     if st != OK:
         raise OombError(st, "oomb_offload_plan")
@@ -296,6 +332,16 @@ def offload_fetch(desc: AttnDesc, host_k_pool, host_v_pool, page_table, plan: "O
                   stage_dk=None, stage_dv=None, stream=None) -> None:
     """oomb_offload_fetch: host_*_pool are pinned host tensors (or device tensors) with the pools' layout; the
     staging pools hold stage_k.shape[0] pages."""
+    if int(stage_k.shape[0]) != plan.capacity:
+        raise OombError(ERR_INVALID_ARG, "oomb_offload_fetch (staging pool size differs from the plan's capacity)")
+    _like("oomb_offload_fetch", "host_v_pool", host_v_pool, host_k_pool)
+    _like("oomb_offload_fetch", "stage_v", stage_v, stage_k)
+    gdt = torch.bfloat16 if desc.grad_dtype == BF16 else torch.float32
+    _like("oomb_offload_fetch", "stage_dk", stage_dk, stage_k, gdt)
+    _like("oomb_offload_fetch", "stage_dv", stage_dv, stage_k, gdt)
+    if tuple(host_k_pool.stride()[1:]) != tuple(stage_k.stride()[1:]) or host_k_pool.dtype != stage_k.dtype or \
+            tuple(stage_k.stride()[:3]) != (desc.pool_page_stride, desc.pool_head_stride, desc.pool_tok_stride):
+        raise OombError(ERR_INVALID_ARG, "oomb_offload_fetch: host and staging pools must share the descriptor's strides and dtype")
     st = lib().oomb_offload_fetch(ctypes.byref(desc), _p(host_k_pool), _p(host_v_pool), _p(page_table), _p(plan.slot_pages),
                                   _p(plan.head_mask), _p(plan.n_slots), int(stage_k.shape[0]), _p(stage_k), _p(stage_v),
                                   _p(stage_dk), _p(stage_dv), _stream_of(stream, stage_k))
@@ -306,6 +352,14 @@ def offload_fetch(desc: AttnDesc, host_k_pool, host_v_pool, page_table, plan: "O
 def offload_writeback(desc: AttnDesc, stage_dk, stage_dv, host_dk_pool, host_dv_pool, page_table, plan: "OffloadPlan",
                       stream=None) -> None:
     """oomb_offload_writeback: host pools += the staged gradient tiles of the held (page, KV head) pairs."""
+    if int(stage_dk.shape[0]) != plan.capacity:
+        raise OombError(ERR_INVALID_ARG, "oomb_offload_writeback (staging pool size differs from the plan's capacity)")
+    gdt = torch.bfloat16 if desc.grad_dtype == BF16 else torch.float32
+    _like("oomb_offload_writeback", "stage_dv", stage_dv, stage_dk, gdt)
+    _like("oomb_offload_writeback", "host_dv_pool", host_dv_pool, host_dk_pool, gdt)
+    if tuple(host_dk_pool.stride()[1:]) != tuple(stage_dk.stride()[1:]) or stage_dk.dtype != gdt or \
+            tuple(stage_dk.stride()[:3]) != (desc.pool_page_stride, desc.pool_head_stride, desc.pool_tok_stride):
+        raise OombError(ERR_INVALID_ARG, "oomb_offload_writeback: host and staging pools must share the descriptor's strides and dtype")
     st = lib().oomb_offload_writeback(ctypes.byref(desc), _p(stage_dk), _p(stage_dv), _p(host_dk_pool), _p(host_dv_pool),
                                       _p(page_table), _p(plan.slot_pages), _p(plan.head_mask), _p(plan.n_slots),
                                       int(stage_dk.shape[0]), _stream_of(stream, stage_dk))
@@ -328,6 +382,7 @@ def paged_attn_fwd_qp(desc: AttnDesc, q, k_pool, v_pool, page_table, sel_pages, 
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((desc.n_q_heads, desc.chunk_len), dtype=torch.float32, device=q.device)
+    _check_family("oomb_paged_attn_fwd_qp", desc, q, k_pool, rows=[("o", o)], pools=[("v_pool", v_pool)], lse=lse)
     stride, m = _qp_lists(desc, sel_pages, sel_count)
     workspace, nbytes = _workspace(desc, stride - m, OP_ATTN_FWD_QP, q.device, workspace)
     st = lib().oomb_paged_attn_fwd_qp(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
@@ -343,6 +398,8 @@ def paged_attn_bwd_qp(desc: AttnDesc, q, k_pool, v_pool, page_table, o, lse, d_o
     """oomb_paged_attn_bwd_qp.  Returns dQ; dk_pool / dv_pool are accumulated in place."""
     if d_q is None:
         d_q = torch.empty_like(q)
+    _check_family("oomb_paged_attn_bwd_qp", desc, q, k_pool, rows=[("o", o), ("d_o", d_o), ("d_q", d_q)],
+                  pools=[("v_pool", v_pool)], grad_pools=[("dk_pool", dk_pool), ("dv_pool", dv_pool)], lse=lse)
     stride, m = _qp_lists(desc, sel_pages, sel_count)
     workspace, nbytes = _workspace(desc, stride - m, OP_ATTN_BWD_QP, q.device, workspace)
     st = lib().oomb_paged_attn_bwd_qp(ctypes.byref(desc), _p(q), _p(k_pool), _p(v_pool), _p(page_table),
@@ -389,6 +446,10 @@ def calibrate(which: int, buf) -> float:
 
 def kv_append(desc: AttnDesc, k_chunk, v_chunk, page_table, k_pool, v_pool, kbar_cache=None) -> None:
     """oomb_kv_append: the chunk's K / V [C][Hkv][D] into its local pages (+ their means into kbar_cache)."""
+    if not (k_chunk.is_contiguous() and v_chunk.is_contiguous()) or k_chunk.shape != v_chunk.shape or \
+            k_chunk.dtype != k_pool.dtype or v_chunk.dtype != k_pool.dtype:
+        raise OombError(ERR_INVALID_ARG, "oomb_kv_append: k_chunk / v_chunk must be contiguous [C][Hkv][D] of the pools' dtype")
+    _like("oomb_kv_append", "v_pool", v_pool, k_pool)
     st = lib().oomb_kv_append(ctypes.byref(desc), _p(k_chunk), _p(v_chunk), _p(page_table), _p(k_pool), _p(v_pool),
                               _p(kbar_cache), _stream(k_pool))
     if st != OK:

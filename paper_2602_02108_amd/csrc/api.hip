@@ -269,6 +269,8 @@ oomb_status oomb_paged_attn_bwd(const oomb_attn_desc* desc, const void* q, const
   if (s != OOMB_OK) return s;
   const bool bf = desc->dtype == OOMB_BF16;
   const bool use_mfma = !force_generic() && mfma_supported(p, bf);
+  // the shape-generic dK/dV kernel walks the list entries in a grid dimension of at most 65535
+  if (!use_mfma && (max_len > 65535 || p.Hkv > 65535)) return OOMB_ERR_UNSUPPORTED;
   const size_t need = use_mfma ? bwd_mfma_workspace_bytes(p, max_len) : up256((size_t)p.Hq * p.C * sizeof(float));
   if (!workspace || workspace_bytes < need || !aligned16(workspace)) return OOMB_ERR_WORKSPACE;
   p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
@@ -355,6 +357,10 @@ oomb_status oomb_paged_attn_bwd_qp(const oomb_attn_desc* desc, const void* q, co
   if (s != OOMB_OK) return s;
   const bool bf = desc->dtype == OOMB_BF16;
   const bool use_mfma = !force_generic() && mfma_supported(p, bf);
+  // grid dimensions of at most 65535: list entries of the shape-generic dK/dV kernel, cut pages of the slice reduction
+  if (p.Hkv > 65535 || (!use_mfma && qp_union_cap(p, sel_stride) > 65535) ||
+      (use_mfma && qp_max_multi(p, sel_stride) > 65535))
+    return OOMB_ERR_UNSUPPORTED;
   if (!workspace || workspace_bytes < qp_workspace_bytes(p, sel_stride, bf, true) || !aligned16(workspace))
     return OOMB_ERR_WORKSPACE;
   p.q = q; p.k_pool = k_pool; p.v_pool = v_pool; p.page_table = page_table;
@@ -378,17 +384,19 @@ oomb_status oomb_paged_attn_bwd_qp(const oomb_attn_desc* desc, const void* q, co
 }
 
 oomb_status oomb_offload_plan(const oomb_attn_desc* desc, const int32_t* sel_pages, const int32_t* sel_count,
-                              int32_t sel_stride, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
-                              uint32_t* head_mask, int32_t* n_slots, void* hip_stream) {
+                              int32_t sel_stride, int32_t lists_per_head, int32_t stage_capacity, int32_t* stage_table,
+                              int32_t* slot_pages, uint32_t* head_mask, int32_t* n_slots, void* hip_stream) {
   Params p{};
   oomb_status s = check_desc(desc, &p);
   if (s != OOMB_OK) return s;
-  if (!sel_pages || !sel_count || sel_stride < p.m || !stage_table || !slot_pages || !head_mask || !n_slots)
+  if (!sel_pages || !sel_count || sel_stride < p.m || stage_capacity <= 0 || !stage_table || !slot_pages || !head_mask ||
+      !n_slots)
     return OOMB_ERR_INVALID_ARG;
   if (lists_per_head != 1 && lists_per_head != p.m) return OOMB_ERR_INVALID_ARG;
   if (p.Hkv > 32 || (int64_t)lists_per_head * sel_stride > INT32_MAX) return OOMB_ERR_UNSUPPORTED;
   p.sel = sel_pages; p.sel_count = sel_count; p.sel_stride = sel_stride;
-  hipError_t e = launch_offload_plan(p, lists_per_head, stage_table, slot_pages, head_mask, n_slots, (hipStream_t)hip_stream);
+  hipError_t e = launch_offload_plan(p, lists_per_head, stage_capacity, stage_table, slot_pages, head_mask, n_slots,
+                                     (hipStream_t)hip_stream);
   return e == hipSuccess ? OOMB_OK : OOMB_ERR_LAUNCH;
 }
 

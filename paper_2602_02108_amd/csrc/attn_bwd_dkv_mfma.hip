@@ -472,14 +472,9 @@ int32_t dkv_splits(const Params& p, int32_t max_len) {
 
 hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
                                float* partial_ws, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_dkv_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)bwd_dkv_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, KV_LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static DeviceOnce lds_once_f32, lds_once_bf16;
+  if (hipError_t e = ensure_max_dynamic_lds(lds_once_f32, (const void*)bwd_dkv_kernel<float>, KV_LDS); e != hipSuccess) return e;
+  if (hipError_t e = ensure_max_dynamic_lds(lds_once_bf16, (const void*)bwd_dkv_kernel<bf16_t>, KV_LDS); e != hipSuccess) return e;
   // (one list per query page: the units come from the device-built table; the grid covers its capacity)
   const int32_t n_split = p.qp ? 1 : dkv_splits(p, max_len);
   float* partial = (p.qp || n_split > 1) ? partial_ws : nullptr;

@@ -363,12 +363,8 @@ size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
 }
 
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, DQ_LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static DeviceOnce lds_once;
+  if (hipError_t e = ensure_max_dynamic_lds(lds_once, (const void*)bwd_dq_kernel, DQ_LDS); e != hipSuccess) return e;
   const int64_t rows_pad = rows_padded(p);
   float* delta_rs = (float*)ws;
   float* lse2_rs = delta_rs + (size_t)p.Hkv * rows_pad;

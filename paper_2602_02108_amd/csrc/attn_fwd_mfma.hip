@@ -328,12 +328,8 @@ size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
 }
 
 hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)fwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FW_LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static DeviceOnce lds_once;
+  if (hipError_t e = ensure_max_dynamic_lds(lds_once, (const void*)fwd_mfma_kernel, FW_LDS); e != hipSuccess) return e;
   const int tiles = row_tiles_per_head(p.C, p.G, p.m, p.qp);
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
   unsigned blocks;

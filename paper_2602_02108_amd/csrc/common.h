@@ -86,6 +86,14 @@ class ProfScope {
   hipEvent_t start_;
 };
 
+// A kernel's dynamic-LDS limit is a per-device function attribute: it is raised once on every device
+// the kernel is launched on, from whichever thread gets there first (implemented in profile.hip).
+struct DeviceOnce {
+  static constexpr int MAX_DEVICES = 64;
+  unsigned char done[MAX_DEVICES] = {};
+};
+hipError_t ensure_max_dynamic_lds(DeviceOnce& once, const void* kernel, int bytes);
+
 // row-space index -> chunk token (row / G) without an integer division
 __device__ __forceinline__ uint32_t div_g(const Params& p, uint32_t r) {
   return p.G == 1 ? r : __umulhi(r, p.g_magic);

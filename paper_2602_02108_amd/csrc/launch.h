@@ -56,8 +56,8 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_
 
 // offload.hip: staging plan and transfers between pinned host pools and device staging pools
 void* device_view(const void* ptr);
-hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
-                               uint32_t* head_mask, int32_t* n_slots, hipStream_t st);
+hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t stage_cap, int32_t* stage_table,
+                               int32_t* slot_pages, uint32_t* head_mask, int32_t* n_slots, hipStream_t st);
 hipError_t launch_offload_fetch(const Params& p, bool is_bf16, const int32_t* slot_pages, const uint32_t* head_mask,
                                 const int32_t* n_slots, int32_t stage_cap, void* host_k, void* host_v, void* stage_k,
                                 void* stage_v, void* stage_dk, void* stage_dv, hipStream_t st);

@@ -51,9 +51,8 @@ __device__ __forceinline__ f32x16 mfma32(const bf16x8& a, const bf16x8& b, const
 // alias any LDS read and waits for them (vmcnt(0)) before the next one, which exposes the whole
 // memory latency.  A kernel that uses these copies has to order them itself: they complete in issue
 // order, so "s_waitcnt vmcnt(n)" followed by a barrier publishes every copy but the n newest.  m0
-// holds the LDS address of such a load; it is a reserved register that the compiler only writes
-// next to an instruction that needs it, and the kernels using these helpers contain no other such
-// instruction.
+// holds the LDS address of such a load; every statement names it as clobbered, so the compiler
+// re-materialises whatever it keeps there itself.
 template <int N>
 __device__ __forceinline__ void copy_kib_to_lds(const unsigned char* src, uint32_t lane_off, uint32_t lds_dst) {
   static_assert(N == 2 || N == 4, "chunks per call");
@@ -63,7 +62,7 @@ __device__ __forceinline__ void copy_kib_to_lds(const unsigned char* src, uint32
         "s_nop 0\n\t"
         "global_load_lds_dwordx4 %1, %2\n\t"
         "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
-        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
+        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory", "m0");
   } else {
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
@@ -72,7 +71,7 @@ __device__ __forceinline__ void copy_kib_to_lds(const unsigned char* src, uint32
         "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
         "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
         "global_load_lds_dwordx4 %1, %2 offset:3072\n\t"
-        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
+        :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory", "m0");
   }
 }
 // one dword per lane (256 bytes per wave)
@@ -81,7 +80,7 @@ __device__ __forceinline__ void copy_256b_to_lds(const unsigned char* src, uint3
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
       "global_load_lds_dword %1, %2\n\t"
-      :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory");
+      :: "s"(lds_dst), "v"(lane_off), "s"(src) : "memory", "m0");
 }
 // at most n of this wave's copies (and other vector-memory operations) are still outstanding
 template <int N> __device__ __forceinline__ void wait_copies() {

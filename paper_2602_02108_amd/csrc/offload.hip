@@ -14,7 +14,10 @@
 // 50 GB/s each way) and disturb only the compute units they sit on.
 //   offload_plan       which KV heads hold each page (bit mask over the lists: one list per
 //                      KV head, or one per KV head and query page) and the staging slot of
-//                      every held page (ascending logical page order), one workgroup
+//                      every held page (ascending logical page order), one workgroup.  The
+//                      slot table is the page table of the staging pools; it never points
+//                      past their capacity (a page that does not fit gets slot 0 and the
+//                      count of held pages tells the caller)
 //   offload_fetch      stage[slot][g] = host[page_table[l]][g]  (K and V) for the held
 //                      (page, head) tiles, optionally zeroing the gradient staging tiles
 //   offload_writeback  host[page_table[l]][g] += stage[slot][g]  (dK and dV)
@@ -28,7 +31,7 @@ namespace oomb {
 constexpr int PLAN_THREADS = 1024;
 
 // lists: p.sel [Hkv][lists_per_head][p.sel_stride], p.sel_count [Hkv][lists_per_head]
-__global__ __launch_bounds__(PLAN_THREADS) void offload_plan_kernel(Params p, int32_t lists_per_head,
+__global__ __launch_bounds__(PLAN_THREADS) void offload_plan_kernel(Params p, int32_t lists_per_head, int32_t stage_cap,
                                                                     int32_t* __restrict__ stage_table,
                                                                     int32_t* __restrict__ slot_pages,
                                                                     uint32_t* __restrict__ head_mask,
@@ -69,14 +72,17 @@ __global__ __launch_bounds__(PLAN_THREADS) void offload_plan_kernel(Params p, in
   int32_t at = before + inc - mine;
   for (int32_t l = l0; l < l1; ++l) {
     if (head_mask[l]) {
-      stage_table[l] = at;
-      slot_pages[at] = l;
+      stage_table[l] = at < stage_cap ? at : 0;
+      if (at < stage_cap) slot_pages[at] = l;
       ++at;
     } else {
       stage_table[l] = -1;
     }
   }
-  if (tid == 0) n_slots[0] = total;
+  if (tid == 0) {
+    n_slots[0] = total < stage_cap ? total : stage_cap;  // slots in use
+    n_slots[1] = total;                                   // pages held: more than stage_cap = overflow
+  }
 }
 
 // Tile (slot s, KV head g): P rows of D elements.  The workgroups walk the tiles with stride gridDim.x.
@@ -166,10 +172,11 @@ static unsigned transfer_wgs(int64_t tiles) {
   return (unsigned)(tiles < v ? (tiles > 0 ? tiles : 1) : v);
 }
 
-hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t* stage_table, int32_t* slot_pages,
-                               uint32_t* head_mask, int32_t* n_slots, hipStream_t st) {
+hipError_t launch_offload_plan(const Params& p, int32_t lists_per_head, int32_t stage_cap, int32_t* stage_table,
+                               int32_t* slot_pages, uint32_t* head_mask, int32_t* n_slots, hipStream_t st) {
   ProfScope prof_("offload_plan", st);
-  offload_plan_kernel<<<dim3(1), dim3(PLAN_THREADS), 0, st>>>(p, lists_per_head, stage_table, slot_pages, head_mask, n_slots);
+  offload_plan_kernel<<<dim3(1), dim3(PLAN_THREADS), 0, st>>>(p, lists_per_head, stage_cap, stage_table, slot_pages, head_mask,
+                                                              n_slots);
   return hipGetLastError();
 }
 

@@ -1,5 +1,6 @@
-// Optional per-kernel timing for benchmarks: when enabled, every kernel launch of
-// the library is bracketed by HIP events recorded on the caller's stream.
+// Host-side services shared by the kernel files: optional per-kernel timing for benchmarks (when
+// enabled, every kernel launch of the library is bracketed by HIP events recorded on the caller's
+// stream) and the once-per-device setup of a kernel's dynamic-LDS limit.
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -45,6 +46,19 @@ void drain(Entry& en) {
   en.pending.clear();
 }
 }  // namespace
+
+hipError_t ensure_max_dynamic_lds(DeviceOnce& once, const void* kernel, int bytes) {
+  static std::mutex mu;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= DeviceOnce::MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (once.done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) once.done[dev] = 1;
+  return e;
+}
 
 ProfScope::ProfScope(const char* name, hipStream_t st) : stream_(st), slot_(-1), start_(nullptr) {
   if (!g_level) return;

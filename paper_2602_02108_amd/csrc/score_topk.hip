@@ -202,15 +202,10 @@ __global__ __launch_bounds__(SELECT_THREADS) void topk_select_kernel(
 
 static hipError_t launch_topk_select(const Params& p, const float* scores, int32_t top_k, int32_t* sel, int32_t* sel_count,
                                      int per_qp, hipStream_t st) {
-  static int lds_cap_bytes = 0;
   constexpr int WANT = 144 * 1024;
-  if (!lds_cap_bytes) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, WANT);
-    lds_cap_bytes = (e == hipSuccess) ? WANT : 48 * 1024;
-    (void)hipGetLastError();
-  }
-  const int64_t cap = lds_cap_bytes / 4;
+  static DeviceOnce lds_once;
+  if (hipError_t e = ensure_max_dynamic_lds(lds_once, (const void*)topk_select_kernel, WANT); e != hipSuccess) return e;
+  const int64_t cap = WANT / 4;
   const int64_t cached = p.n_past < cap ? p.n_past : cap;
   ProfScope prof_("topk_select", st);
   topk_select_kernel<<<dim3((unsigned)(per_qp ? p.Hkv * p.m : p.Hkv)), dim3(SELECT_THREADS), (size_t)cached * 4, st>>>(
@@ -220,19 +215,22 @@ static hipError_t launch_topk_select(const Params& p, const float* scores, int32
 
 // kbar_cache != nullptr: the page means come from the cache instead of the keys
 template <typename T, int D>
-static void launch_scoring(const Params& p, float* A, float* qbar, float* scores, const float* kbar_cache, hipStream_t st) {
+static hipError_t launch_scoring(const Params& p, float* A, float* qbar, float* scores, const float* kbar_cache, hipStream_t st) {
   constexpr int VEC = Vec16<T>::N, LPR = D / VEC, PER_BLOCK = 256 / LPR;
   const int units = p.Hq * p.m;
   { ProfScope prof_("qpool_partial", st); qpool_partial_kernel<T, D><<<dim3((units + PER_BLOCK - 1) / PER_BLOCK), dim3(256), 0, st>>>(p, A); }
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   const float r = 1.0f / (float)((int64_t)p.C * p.G);
   { ProfScope prof_("qpool_final", st); qpool_final_kernel<<<dim3(p.Hkv), dim3(D), 0, st>>>(p, A, qbar, r); }
-  if (kbar_cache) {
-    (void)launch_page_score_cached(p, qbar, kbar_cache, scores, st);
-  } else if (p.n_past > 0) {
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  if (kbar_cache) return launch_page_score_cached(p, qbar, kbar_cache, scores, st);
+  if (p.n_past > 0) {
     const float inv_p = 1.0f / (float)p.P;
     dim3 grid((unsigned)((p.n_past + PER_BLOCK - 1) / PER_BLOCK), p.Hkv);
     { ProfScope prof_("page_score", st); page_score_kernel<T, D><<<grid, dim3(256), 0, st>>>(p, qbar, scores, inv_p); }
+    return hipGetLastError();
   }
+  return hipSuccess;
 }
 
 size_t score_workspace_bytes(const Params& p) {
@@ -254,13 +252,15 @@ hipError_t launch_score_topk(const Params& p, bool is_bf16, int32_t top_k, int32
   w += up((size_t)p.Hkv * p.D * sizeof(float));
   float* scores = scores_out ? scores_out : (float*)w;
 
+  hipError_t e;
   if (is_bf16) {
-    if (p.D == 128) launch_scoring<bf16_t, 128>(p, A, qbar, scores, kbar_cache, st);
-    else launch_scoring<bf16_t, 64>(p, A, qbar, scores, kbar_cache, st);
+    e = p.D == 128 ? launch_scoring<bf16_t, 128>(p, A, qbar, scores, kbar_cache, st)
+                   : launch_scoring<bf16_t, 64>(p, A, qbar, scores, kbar_cache, st);
   } else {
-    if (p.D == 128) launch_scoring<float, 128>(p, A, qbar, scores, kbar_cache, st);
-    else launch_scoring<float, 64>(p, A, qbar, scores, kbar_cache, st);
+    e = p.D == 128 ? launch_scoring<float, 128>(p, A, qbar, scores, kbar_cache, st)
+                   : launch_scoring<float, 64>(p, A, qbar, scores, kbar_cache, st);
   }
+  if (e != hipSuccess) return e;
   return launch_topk_select(p, scores, top_k, sel, sel_count, 0, st);
 }
 

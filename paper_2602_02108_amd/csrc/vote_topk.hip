@@ -297,14 +297,9 @@ hipError_t launch_vote_topk(Params p, bool is_bf16, bool force_generic, const fl
   float* votes = votes_out ? votes_out : (float*)(b + L.off_votes);
   p.qp = 0;
   if (p.n_past > 0 && mfma) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)vote_pass_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, VT_LDS);
-      if (e != hipSuccess) return e;
-      e = hipFuncSetAttribute((const void*)vote_pass_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, VT_LDS);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    static DeviceOnce lds_once_1, lds_once_2;
+    if (hipError_t e = ensure_max_dynamic_lds(lds_once_1, (const void*)vote_pass_kernel<1>, VT_LDS); e != hipSuccess) return e;
+    if (hipError_t e = ensure_max_dynamic_lds(lds_once_2, (const void*)vote_pass_kernel<2>, VT_LDS); e != hipSuccess) return e;
     unsigned char* img = b + L.off_img;
     float* lse2 = (float*)(b + L.off_lse);
     float* part = (float*)(b + L.off_part);

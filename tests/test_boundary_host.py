@@ -157,9 +157,11 @@ def test_offload_entry_points_validate_before_launch():
     fake = ctypes.c_void_p(0x1000)
     m = 4096 // 128
     # plan: row stride that cannot hold the local pages; missing counts; lists per head neither 1 nor m
-    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 8, 1, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
-    assert l.oomb_offload_plan(ctypes.byref(d), fake, None, 64 + m, 1, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
-    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 64 + m, 3, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 8, 1, 640, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, None, 64 + m, 1, 640, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 64 + m, 3, 640, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
+    # staging pools without a page
+    assert l.oomb_offload_plan(ctypes.byref(d), fake, fake, 64 + m, 1, 0, fake, fake, fake, fake, None) == api.ERR_INVALID_ARG
     # gradient staging pools come in pairs
     assert l.oomb_offload_fetch(ctypes.byref(d), fake, fake, fake, fake, fake, fake, 640, fake, fake, fake, None,
                                 None) == api.ERR_INVALID_ARG
@@ -197,3 +199,26 @@ def test_noalloc_scoring_refuses_shapes_beyond_its_scratch():
     # bad arguments are still reported first
     st = api.lib().oomb_page_score_topk_noalloc(ctypes.byref(_good_desc()), fake, None, fake, 8, fake, fake, None, None)
     assert st == api.ERR_INVALID_ARG
+
+
+def test_binding_refuses_tensors_that_do_not_share_the_descriptor_layout():
+    """One stride set per tensor family: a dO that comes out of autograd with other strides, a gradient pool of
+    another dtype or a differently padded V pool would be addressed wrongly, so the binding refuses them."""
+    import torch
+    C, Hq, Hkv, D, P, n = 32, 2, 1, 64, 16, 4
+    q = torch.zeros(C, Hq, D)
+    k = torch.zeros(n, Hkv, P, D)
+    desc = api.make_desc(q, k, n * P, 0.125)
+    pt = torch.arange(n, dtype=torch.int32)
+    lse = torch.zeros(Hq, C)
+    strided = torch.zeros(C, Hq, 2 * D)[:, :, :D]            # same shape, other strides
+    with pytest.raises(api.OombError, match="d_o"):
+        api.paged_attn_bwd(desc, q, k, k, pt, q, lse, strided, k.clone(), k.clone())
+    with pytest.raises(api.OombError, match="dk_pool"):
+        api.paged_attn_bwd(desc, q, k, k, pt, q, lse, q, k.to(torch.bfloat16), k.clone())
+    with pytest.raises(api.OombError, match="v_pool"):
+        api.paged_attn_fwd(desc, q, k, torch.zeros(n, Hkv, P + 1, D)[:, :, :P], pt)
+    with pytest.raises(api.OombError, match="lse"):
+        api.paged_attn_bwd(desc, q, k, k, pt, q, lse.double(), q, k.clone(), k.clone())
+    with pytest.raises(api.OombError, match="descriptor"):
+        api.paged_attn_fwd(desc, strided, k, k, pt)

@@ -148,7 +148,6 @@ def test_captured_offloaded_step_replays_like_the_eager_step():
     stage_v = torch.zeros_like(stage_k)
     stage_dk = torch.zeros(shape, dtype=gdt, device=dev)
     stage_dv = torch.zeros_like(stage_dk)
-    staged_table = torch.zeros(w.n, dtype=torch.int32, device=dev)
     o = torch.empty_like(x["q"])
     lse = torch.empty((w.Hq, w.C), dtype=torch.float32, device=dev)
     dq = torch.empty_like(x["q"])
@@ -157,9 +156,8 @@ def test_captured_offloaded_step_replays_like_the_eager_step():
         api.page_score_topk_cached(desc, x["q"], cache, w.top_k, sel, cnt, workspace=ws[api.OP_SCORE_TOPK])
         api.offload_plan(desc, sel, cnt, plan=plan)
         api.offload_fetch(desc, host_k, host_v, x["page_table"], plan, stage_k, stage_v, stage_dk, stage_dv)
-        torch.clamp(plan.stage_table, min=0, out=staged_table)
-        api.paged_attn_fwd(desc, x["q"], stage_k, stage_v, staged_table, sel, cnt, o, lse, ws[api.OP_ATTN_FWD])
-        api.paged_attn_bwd(desc, x["q"], stage_k, stage_v, staged_table, o, lse, x["d_o"], stage_dk, stage_dv, sel, cnt,
+        api.paged_attn_fwd(desc, x["q"], stage_k, stage_v, plan.stage_table, sel, cnt, o, lse, ws[api.OP_ATTN_FWD])
+        api.paged_attn_bwd(desc, x["q"], stage_k, stage_v, plan.stage_table, o, lse, x["d_o"], stage_dk, stage_dv, sel, cnt,
                            dq, ws[api.OP_ATTN_BWD])
         api.offload_writeback(desc, stage_dk, stage_dv, host_dk, host_dv, x["page_table"], plan)
 

@@ -42,6 +42,18 @@ def _setup(w):
     return x, desc, sel, cnt
 
 
+def _plan_arrays(w, hsel, hcnt):
+    """What oomb_offload_plan must write, derived here from the lists: the mask of the KV heads that hold each
+    page and the held pages in ascending order (the oracle itself works on the lists)."""
+    mask = np.zeros(w.n, np.uint32)
+    for g in range(w.Hkv):
+        lists = hsel[g].reshape(-1, hsel.shape[-1])
+        for lst, c in zip(lists, hcnt[g].reshape(-1)):
+            for l in lst[:c]:
+                mask[l] |= np.uint32(1 << g)
+    return mask, np.flatnonzero(mask).astype(np.int32)
+
+
 def _check_movement(w, x, desc, sel, cnt):
     """plan / fetch / write-back against the oracle, bit for bit, for lists of either shape."""
     hx = pu.host_inputs(x)
@@ -49,9 +61,12 @@ def _check_movement(w, x, desc, sel, cnt):
     hsel, hcnt = sel.cpu().numpy(), cnt.cpu().numpy()
     plan = api.offload_plan(desc, sel, cnt)
     torch.cuda.synchronize()
-    otable, oslots, omask = orc.offload_plan(sh, hsel, hcnt)
-    ns = int(plan.n_slots.item())
-    assert ns == len(oslots) <= plan.capacity
+    otable, n_union = orc.offload_stage_table(sh, hsel, hcnt)
+    omask, oslots = _plan_arrays(w, hsel, hcnt)
+    assert n_union == len(oslots)
+    ns = plan.n_slots.cpu().numpy()
+    assert ns[0] == ns[1] == n_union <= plan.capacity and not plan.overflowed()
+    ns = int(ns[0])
     assert np.array_equal(plan.stage_table.cpu().numpy(), otable)
     assert np.array_equal(plan.slot_pages.cpu().numpy()[:ns], oslots)
     assert np.array_equal(plan.head_mask.cpu().numpy().view(np.uint32), omask)
@@ -67,7 +82,7 @@ def _check_movement(w, x, desc, sel, cnt):
     before = [t.clone() for t in (stage_k, stage_v, stage_dk, stage_dv)]
     api.offload_fetch(desc, host_k, host_v, x["page_table"], plan, stage_k, stage_v, stage_dk, stage_dv)
     torch.cuda.synchronize()
-    ok, ov = orc.offload_fetch(sh, hx["k_pool"], hx["v_pool"], hx["page_table"], oslots, omask,
+    ok, ov = orc.offload_fetch(sh, hx["k_pool"], hx["v_pool"], hx["page_table"], hsel, hcnt,
                                to_numpy(before[0]), to_numpy(before[1]))
     assert np.array_equal(_bits(to_numpy(stage_k)), _bits(ok)) and np.array_equal(_bits(to_numpy(stage_v)), _bits(ov))
     # gradient staging: held tiles zeroed, the rest untouched
@@ -87,8 +102,8 @@ def _check_movement(w, x, desc, sel, cnt):
     host_dk, host_dv = _pinned(h0k), _pinned(h0v)
     api.offload_writeback(desc, stage_dk, stage_dv, host_dk, host_dv, x["page_table"], plan)
     torch.cuda.synchronize()
-    wk, wv = orc.offload_writeback(sh, before[2].float().cpu().numpy()[:ns], before[3].float().cpu().numpy()[:ns],
-                                   h0k.float().numpy(), h0v.float().numpy(), hx["page_table"], oslots, omask)
+    wk, wv = orc.offload_writeback(sh, before[2].float().cpu().numpy(), before[3].float().cpu().numpy(),
+                                   h0k.float().numpy(), h0v.float().numpy(), hx["page_table"], hsel, hcnt)
     if w.grad_dtype == "bf16":  # the sum is rounded to the pool's dtype
         wk = torch.from_numpy(wk).to(torch.bfloat16).float().numpy()
         wv = torch.from_numpy(wv).to(torch.bfloat16).float().numpy()
@@ -131,7 +146,7 @@ def _offloaded_pass(w, x, desc, sel, cnt, qp):
     fetched = torch.cuda.Event()
     fetched.record(copy_stream)
     main.wait_event(fetched)
-    staged_pt = plan.stage_table.clamp(min=0)
+    staged_pt = plan.stage_table    # the plan's slot table is the page table of the staging pools
     fwd = api.paged_attn_fwd_qp if qp else api.paged_attn_fwd
     bwd = api.paged_attn_bwd_qp if qp else api.paged_attn_bwd
     o, lse = fwd(desc, x["q"], stage_k, stage_v, staged_pt, sel, cnt)
@@ -191,3 +206,48 @@ def test_host_pools_that_the_device_cannot_address_are_refused():
     with pytest.raises(api.OombError):
         api.offload_fetch(desc, pageable, pageable, x["page_table"], plan, stage, stage.clone())
     torch.cuda.synchronize()
+
+
+def test_staging_pools_that_are_too_small_are_reported_and_never_overrun():
+    """Fewer slots than held pages: the plan says so (pages held > capacity), its table stays inside the pools,
+    fetch and write-back move the pages that fit -- compared with the oracle given the same capacity -- and
+    memory behind the staging pools is untouched."""
+    w = CASES[1]
+    x, desc, sel, cnt = _setup(w)
+    hx = pu.host_inputs(x)
+    sh = pu.shape_of(w)
+    hsel, hcnt = sel.cpu().numpy(), cnt.cpu().numpy()
+    _, n_union = orc.offload_stage_table(sh, hsel, hcnt)
+    cap = n_union - 3
+    assert cap > 0
+    plan = api.OffloadPlan(desc, cap, "cuda")
+    api.offload_plan(desc, sel, cnt, plan=plan)
+    torch.cuda.synchronize()
+    otable, _ = orc.offload_stage_table(sh, hsel, hcnt, capacity=cap)
+    assert plan.overflowed() and plan.n_slots.cpu().tolist() == [cap, n_union]
+    table = plan.stage_table.cpu().numpy()
+    assert np.array_equal(table, otable) and table.max() < cap
+    # staging pools with a guard page behind them
+    shape = (cap + 1,) + tuple(x["k_pool"].shape[1:])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    big_k = torch.randn(shape, generator=g, device="cuda").to(x["k_pool"].dtype)
+    big_v = torch.randn(shape, generator=g, device="cuda").to(x["k_pool"].dtype)
+    was_k, was_v = big_k.clone(), big_v.clone()
+    host_k, host_v = _pinned(x["k_pool"]), _pinned(x["v_pool"])
+    api.offload_fetch(desc, host_k, host_v, x["page_table"], plan, big_k[:cap], big_v[:cap])
+    torch.cuda.synchronize()
+    ok, ov = orc.offload_fetch(sh, hx["k_pool"], hx["v_pool"], hx["page_table"], hsel, hcnt,
+                               to_numpy(was_k[:cap]), to_numpy(was_v[:cap]))
+    assert np.array_equal(_bits(to_numpy(big_k[:cap])), _bits(ok)) and np.array_equal(_bits(to_numpy(big_v[:cap])), _bits(ov))
+    assert torch.equal(big_k[cap], was_k[cap]) and torch.equal(big_v[cap], was_v[cap])
+    gdt = torch_dtype(w.grad_dtype)
+    sdk = torch.randn(shape, generator=g, device="cuda").to(gdt)
+    sdv = torch.randn(shape, generator=g, device="cuda").to(gdt)
+    h0 = torch.randn(x["k_pool"].shape, generator=torch.Generator().manual_seed(12)).to(gdt)
+    host_dk, host_dv = _pinned(h0), _pinned(h0)
+    api.offload_writeback(desc, sdk[:cap], sdv[:cap], host_dk, host_dv, x["page_table"], plan)
+    torch.cuda.synchronize()
+    wk, wv = orc.offload_writeback(sh, sdk[:cap].float().cpu().numpy(), sdv[:cap].float().cpu().numpy(), h0.float().numpy(),
+                                   h0.float().numpy(), hx["page_table"], hsel, hcnt)
+    assert np.array_equal(host_dk.float().numpy(), wk) and np.array_equal(host_dv.float().numpy(), wv)
