@@ -15,9 +15,11 @@
  *   t <= a_i and logical page t / P is in the selection list of KV head g.
  *
  * Memory: EVERY pointer below is DEVICE memory owned by the caller (except the
- * descriptor, which is host memory read during the call).  The library never
- * allocates, frees or synchronises; all work is enqueued on `hip_stream`
- * (a hipStream_t; NULL = the default stream) and the call returns at once.
+ * descriptor, which is host memory read during the call).  No entry point of this
+ * header allocates, frees or synchronises; all work is enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream) and the call returns at once.  (The
+ * benchmark aids of oomb_bench.h -- per-kernel event timing, measured ceilings --
+ * are kept apart because they do wait for the device.)
  * Layouts (element strides given in the descriptor, D always contiguous):
  *   Q, O, dO, dQ      [C][Hq][D]       q_tok_stride, q_head_stride
  *   K/V pools         [n_phys][Hkv][P][D]  pool_page_stride, pool_head_stride, pool_tok_stride
@@ -359,42 +361,6 @@ oomb_status oomb_offload_writeback(const oomb_attn_desc* desc, const void* stage
 oomb_status oomb_check_inputs(const oomb_attn_desc* desc, const int32_t* page_table, const int32_t* sel_pages,
                               const int32_t* sel_count, int32_t sel_stride, int32_t lists_per_head, int32_t* violations,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
-
-/*
- * Benchmark aid (not part of the paper's method): per-kernel device time.  While
- * enabled (on = 1), every kernel the library launches is bracketed by two HIP events
- * recorded on the caller's stream (events are host objects created on demand; no
- * device memory is allocated).  on = 2 brackets only the four large kernels (page
- * scoring, forward, dQ, dK/dV), which disturbs back-to-back launches less; on = 0
- * switches the timing off.  oomb_profile_read waits for the recorded events of
- * entry idx (0 <= idx < oomb_profile_count()) and returns the kernel's name, its
- * accumulated device time in milliseconds and its launch count; it returns
- * OOMB_ERR_INVALID_ARG for a bad index or NULL outputs.  oomb_profile_reset drops
- * all entries.  Not thread-safe against concurrent launches on other threads.
- */
-void oomb_profile_enable(int32_t on);
-void oomb_profile_reset(void);
-int32_t oomb_profile_count(void);
-int32_t oomb_profile_read(int32_t idx, char* name, int32_t name_cap, double* total_ms, int64_t* launches);
-
-/*
- * Benchmark aid (not part of the paper's method): a measured ceiling of the device,
- * to set kernel rates against something other than the data-sheet peaks.
- *   which = 0: every SIMD issues independent 32x32x16 bf16 matrix instructions back
- *              to back on constant operands; *result = TFLOP/s.  buf is only a sink
- *              (>= 4096 bytes).
- *   which = 2: the same instruction stream on operands with random signs and mantissas
- *              that change from one instruction to the next (the clock of the part
- *              follows the switching activity of the matrix units, so this is the
- *              ceiling of a kernel that multiplies real data); *result = TFLOP/s.
- *   which = 1: a streaming kernel copies the first half of buf (device memory,
- *              16-byte aligned, `bytes` long) to its second half; *result = GB/s
- *              counting bytes read + bytes written.
- * Runs on hip_stream and WAITS for the measurement (one warm-up launch, one timed
- * launch).  Returns OOMB_ERR_INVALID_ARG for NULL / misaligned / too small buffers
- * or an unknown `which`, OOMB_ERR_LAUNCH if HIP reports an error.
- */
-oomb_status oomb_calibrate(int32_t which, void* buf, size_t bytes, double* result, void* hip_stream);
 
 const char* oomb_status_string(int32_t status);
 

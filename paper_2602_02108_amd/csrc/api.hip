@@ -477,6 +477,6 @@ const char* oomb_status_string(int32_t status) {
   }
 }
 
-int32_t oomb_version(void) { return 100; }
+int32_t oomb_version(void) { return 200; }
 
 }  // extern "C"

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/oomb.h"
+#include "../../include/oomb_bench.h"
 
 namespace oomb {
 
