@@ -448,7 +448,10 @@ __global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(Params p, const flo
                            (int64_t)key * p.pool_tok_stride + d4;
   float4 s = {0.f, 0.f, 0.f, 0.f};
   for (int sp = 0; sp < n_split; ++sp) {
-    const float4 v = *reinterpret_cast<const float4*>(partial + ((first_part + sp) * 2 + which) * (TP * HD) + key * HD + d4);
+    // (read once: non-temporal, so that the partial pages do not push anything else out of the caches)
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    const f32x4_t v = __builtin_nontemporal_load(
+        reinterpret_cast<const f32x4_t*>(partial + ((first_part + sp) * 2 + which) * (TP * HD) + key * HD + d4));
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   TG* pool = (TG*)(which == 0 ? p.dk_pool : p.dv_pool) + pool_off;

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void page_means_vec_kernel(Params p, int64_t f
   const T* base = (const T*)p.k_pool + (int64_t)p.page_table[l] * p.pool_page_stride +
                   (int64_t)g * p.pool_head_stride + lr * VEC;
   float x[VEC];
-  seq_row_sum<T, 8>(base, p.pool_tok_stride, p.P, x);
+  seq_row_sum<T, 8, true>(base, p.pool_tok_stride, p.P, x);
   float* out = cache + ((int64_t)l * p.Hkv + g) * D + lr * VEC;
 #pragma unroll
   for (int v = 0; v < VEC; ++v) out[v] = __fmul_rn(x[v], inv_p);
