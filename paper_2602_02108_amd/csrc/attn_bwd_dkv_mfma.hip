@@ -21,24 +21,27 @@
 // once, together with the swizzled Q / dO tile images, by a layout kernel) straight into
 // the accumulator registers.
 //
-// LDS: two stages of 64 query rows x {Q natural, dO natural, Q transposed, dO
-// transposed} (16 KiB each) + the P exchange (4 pairs x 2 x 2 KiB) + bias words = 145 KiB.  The
-// natural tiles of both stages sit in the lower 64 KiB and the transposed tiles in
-// the next 64 KiB, so that every operand address is a loop-invariant register plus
-// an immediate; the loops are unrolled by two stages to make the stage a constant.
+// LDS: four stage buffers of 64 query rows x {Q, dO} (16 KiB each, rows in natural order) + the
+// P exchange (4 pairs x 2 x 2 KiB) + bias words = 146 KiB.  Both products of a role read the same
+// tiles: the chain takes whole rows (16-byte reads), the transposed-tile product takes its
+// operand with the transposing LDS read of gfx950 (ds_read_b64_tr_b16: 16 lanes hand in 16 rows
+// of four 16-bit words and get back four rows of one column each), so no transposed copy of Q / dO
+// exists anywhere.  The Q tiles of all buffers sit in the lower 64 KiB and the dO tiles in the
+// next 64 KiB, so that every operand address is a loop-invariant register plus an immediate below
+// 64 KiB; the loops are unrolled by four stages to make the buffer a constant.
 #include "mfma_common.h"
 #include "launch.h"
 
 namespace oomb {
 
 constexpr int KV_THREADS = 512;
-constexpr int KV_TR = 65536;                   // first transposed tile
+constexpr int KV_BUFS = 4;                     // stage buffers
+constexpr int KV_DO = 65536;                   // first dO tile (the Q tiles start at 0)
 constexpr int KV_XCH = 131072;                 // P exchange
 constexpr int KV_BIAS = KV_XCH + 4 * 2 * 2048;  // bias words: [stage buffer][role][64 rows]
-constexpr int KV_LDS = KV_BIAS + 2 * 512;
-// tile offsets: natural Q / dO of stage st, transposed Q / dO of stage st (relative to KV_TR)
-__device__ __forceinline__ constexpr int kv_nat(int st, int which) { return st * 32768 + which * 16384; }
-__device__ __forceinline__ constexpr int kv_tr(int st, int which) { return st * 32768 + which * 16384; }
+constexpr int KV_LDS = KV_BIAS + KV_BUFS * 512;
+// offset of block `half` of stage buffer st inside the Q tiles or the dO tiles
+__device__ __forceinline__ constexpr int kv_blk(int st, int half) { return st * 16384 + half * 8192; }
 
 __device__ __forceinline__ uint4 kv_pack8(const f32x16& v, int base) {
   uint4 w;
@@ -158,39 +161,73 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 #pragma unroll
     for (int x = 0; x < 16; ++x) acc[db][x] = 0.f;
 
-  // LDS operand addresses: (lane base ^ constant) + immediate
-  uint32_t na[8], ta[4];
+  // LDS operand addresses: (lane base ^ constant) + immediate.  Granule c (dims 8c .. 8c+7) of row r
+  // of a 32-row block sits at granule position c ^ f(r), f(r) = 4 (r % 4) + (r / 4) % 4.
+  //  - chain operand (rows of the tile): lane (lq, hh) reads granule 2 kk + hh of row lq; 16
+  //    consecutive rows spread over all 16 positions.
+  //  - transposed operand: the lane must end up with column 32 db + lane % 32 of the rows
+  //    16 u + 8 r + 4 hh + {0..3} (read r = 0, 1), the order in which its partner's accumulator
+  //    registers hold the rows.  The transposing read returns to lane i of a group of 16 word i % 4
+  //    of the 8 bytes addressed by lanes i / 4 + {0, 4, 8, 12} of the group; so lane L of group gq
+  //    addresses row 16 u + 8 r + 4 (gq / 2) + L / 4, columns 32 db + 16 (gq % 2) + 4 (L % 4) .. + 3.
+  //    The 32 lanes served together touch 4 rows x 64 bytes, which f spreads over all banks.
+  uint32_t na[8], tt[8];
   {
-    const uint32_t nbase = lq * 256 + (((lq & 15) ^ hh) << 4);          // natural tiles, 16 granules per row
-    const uint32_t tbase = lq * 128 + ((((lq >> 1) & 7) ^ hh) << 4);    // transposed tiles, 8 granules per row
+    const uint32_t f = ((lq & 3) << 2) | ((lq >> 2) & 3);
+    const uint32_t nbase = lq * 256 + ((f ^ hh) << 4) + (role == 0 ? 0 : KV_DO);   // role 0 chains on Q, role 1 on dO
 #pragma unroll
     for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
+    const uint32_t L = lane & 15, gq = lane >> 4;
+    const uint32_t trow = 4 * (gq >> 1) + (L >> 2);
+    const uint32_t tgran = (2 * (gq & 1) + ((L & 3) >> 1)) ^ (((L >> 2) << 2) | (gq >> 1));
+    const uint32_t tbase = trow * 256 + (tgran << 4) + 8 * (L & 1) + (role == 0 ? KV_DO : 0);  // role 0: dO^T, role 1: Q^T
 #pragma unroll
-    for (int k = 0; k < 4; ++k) ta[k] = (tbase ^ (k << 5)) + KV_TR;
+    for (int db = 0; db < 4; ++db) {
+      tt[2 * db] = tbase ^ (db << 6);            // rows 16 u + 4 hh + {0..3}
+      tt[2 * db + 1] = tbase ^ (db << 6) ^ 32;   // rows 16 u + 8 + 4 hh + {0..3}: + 2048 as an immediate
+    }
   }
   const uint32_t xo = KV_XCH + kbw * 4096 + lane * 16;  // this pair's P exchange, this lane's 16 bytes
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  // Staging.  The query-side tiles of a stage (Q and dO, natural and transposed, already swizzled)
-  // and its bias words are one contiguous image per (KV head, stage).  It is copied with direct
-  // global -> LDS loads (no staging registers, so a whole stage of copies can be in flight): every
-  // wave moves 4 KiB of the natural half and 4 KiB of the transposed half, waves 0 and 1 also the
-  // bias words.  This kernel orders the copies itself: they complete in issue order, so "at most n
-  // outstanding" before a barrier publishes everything older than the newest n.
-  constexpr int IMG_BYTES = 65536, IMG_STRIDE = IMG_BYTES + 512;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  // transposed fragment (dim block and read r folded into `addr`): eight 16-bit words of one column
+  auto tr_frag = [&](const uint32_t addr_r0, const uint32_t addr_r1, const int off) __attribute__((always_inline)) -> u32x4 {
+    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(smem + (addr_r0 + off))));
+    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(smem + (addr_r1 + (off + 2048)))));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+  };
+  // Staging.  The query-side tiles of a stage (Q and dO, already swizzled) and its bias words are
+  // one contiguous image per (KV head, stage).  It is copied with direct global -> LDS loads (no
+  // staging registers, so several stages of copies can be in flight): every wave moves 4 KiB,
+  // waves 0 and 1 also the bias words.  This kernel orders the copies itself: they complete in
+  // issue order, so "at most n outstanding" before a barrier publishes everything older than the
+  // newest n.
+  constexpr int IMG_BYTES = 32768, IMG_STRIDE = IMG_BYTES + 512;
   const unsigned char* img_g = img + (int64_t)g * n_stages * IMG_STRIDE;
-  const uint32_t cp_off = 4096 * wave + 16 * lane;  // lane offset inside either half of an image
+  const uint32_t cp_off = 4096 * wave + 16 * lane;  // lane offset inside an image
   const uint32_t cp_bias = 256 * wave + 4 * lane;   // (waves 0, 1) lane offset inside the bias words
-  // natural half of stage s -> stage buffer st.  Its readers finished before the last barrier.
-  auto copy_natural = [&](const int32_t s, const int st) __attribute__((always_inline)) {
+  const uint32_t cp_dst = (wave >> 2) * KV_DO + (wave & 3) * 4096;   // waves 0..3 move Q, 4..7 dO
+  // stage s -> stage buffer st.  The buffer's last readers must have passed a barrier.
+  auto copy_stage = [&](const int32_t s, const int st) __attribute__((always_inline)) {
     const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE;
-    copy_kib_to_lds<4>(base, cp_off, st * 32768 + 4096 * wave);
+    copy_kib_to_lds<4>(base, cp_off, st * 16384 + cp_dst);
     if (wave < 2) copy_256b_to_lds(base + IMG_BYTES, cp_bias, KV_BIAS + st * 512 + 256 * wave);
   };
-  // transposed half of stage s -> stage buffer st.  Only legal after the first barrier of the stage
-  // that precedes s: until then the previous contents are still read.
-  auto copy_transposed = [&](const int32_t s, const int st) __attribute__((always_inline)) {
-    copy_kib_to_lds<4>(img_g + (int64_t)s * IMG_STRIDE + 32768, cp_off, KV_TR + st * 32768 + 4096 * wave);
+  // all but the newest n stages of copies have landed (a stage is 4 loads, 5 for waves 0 and 1)
+  auto wait_stages = [&](const int n) __attribute__((always_inline)) {
+    if (n >= 2) {
+      if (wave < 2) wait_copies<10>();
+      else wait_copies<8>();
+    } else if (n == 1) {
+      if (wave < 2) wait_copies<5>();
+      else wait_copies<4>();
+    } else {
+      wait_copies<0>();
+    }
   };
   // this role's bias words of block `half` of stage buffer st, as the initial value of a (query x key)
   // accumulator: register x belongs to row 8 (x / 4) + 4 hh + x % 4 of the block
@@ -202,70 +239,62 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       chain[4 * a + 0] = v.x; chain[4 * a + 1] = v.y; chain[4 * a + 2] = v.z; chain[4 * a + 3] = v.w;
     }
   };
-  // barrier between the two steps of a stage: the transposed half of this stage (issued one stage
-  // ago) must have landed; the natural half of the next stage (4 loads, 5 for waves 0 and 1) may
-  // still be in flight.  Barrier at the end of a stage: that natural half must have landed, the
-  // transposed half issued after the first barrier (4 loads) may be in flight.
-  auto mid_barrier = [&](const bool more) __attribute__((always_inline)) {
-    if (!more) wait_copies<0>();
-    else if (wave < 2) wait_copies<5>();
-    else wait_copies<4>();
-    __syncthreads();
-  };
-  auto end_barrier = [&]() __attribute__((always_inline)) {
-    wait_copies<4>();
-    __syncthreads();
-  };
 
-  // Both roles multiply the transposed tiles of the previous block one step late; in the very first
-  // step that "previous block" is zeros times the transposed tiles of the second stage buffer.  Clear
-  // those tiles and the P exchange so that no stale NaN pattern is read.
+  // Both roles multiply the transposed tile of the previous block one step late; in the very first
+  // step that "previous block" is zeros times block 1 of the last stage buffer.  Clear those
+  // blocks and the P exchange so that no stale NaN pattern is read.
   {
     const uint4 z = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + KV_TR + kv_tr(1, 0) + tid * 64 + 16 * k) = z;
+    unsigned char* blk = smem + ((tid >> 8) * KV_DO + kv_blk(KV_BUFS - 1, 1) + (tid & 255) * 32);
+    *reinterpret_cast<uint4*>(blk) = z;
+    *reinterpret_cast<uint4*>(blk + 16) = z;
     if (role == 0) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) *reinterpret_cast<uint4*>(smem + (xo + k * 1024)) = z;
     }
   }
-  int32_t rs = real_first();  // real stage of the stage being computed
-  if (nb > 0) {
-    copy_natural(rs, 0);
-    copy_transposed(rs, 0);
-  }
+  // real stages of the stage being computed and of the two after it (their copies are under way)
+  int32_t rs = real_first(), rs1 = real_next(rs), rs2 = real_next(rs1);
+  const int32_t n_st = s1 - s0;
+  // (every load issued so far -- the K / V rows -- is waited for here, once, so that no wait for
+  // them is left inside the loops, where it would drain the copies under way)
   wait_copies<0>();
+  if (n_st > 0) copy_stage(rs, 0);
+  if (n_st > 1) copy_stage(rs1, 1);
+  if (n_st > 2) copy_stage(rs2, 2);
+  wait_stages(n_st > 2 ? 2 : n_st - 1);
   __syncthreads();
 
   // The matrix phase of a step, the same for both roles: the accumulator chain of the current block
-  // (S = bias + Q K^T for role 0, dP = bias + dO V^T for role 1: A = natural rows of tile `natw`,
+  // (S = bias + Q K^T for role 0, dP = bias + dO V^T for role 1: A = rows of the role's chain tile,
   // B = this wave's K or V rows) interleaved with the transposed-tile product of the PREVIOUS block
-  // (dV^T += dO^T P resp. dK^T += Q^T dS: A = transposed rows of tile `trw`, B = b0 / b1), so that
-  // neighbouring matrix instructions never depend on each other.  Batch j of four: k-steps 2j, 2j+1 of
-  // the chain, dim blocks 2 (j % 2), + 1 of key group j / 2.  One batch is fetched ahead; one wait per
-  // batch.  The previous block of half 0 is block 1 of the other stage buffer.
+  // (dV^T += dO^T P resp. dK^T += Q^T dS: A = transposed reads of the role's other tile, B = b0 / b1),
+  // so that neighbouring matrix instructions never depend on each other.  Batch j of four: k-steps
+  // 2j, 2j+1 of the chain, dim blocks 2 (j % 2), + 1 of key group j / 2.  One batch is fetched ahead;
+  // one wait per batch.  The previous block of half 0 is block 1 of the previous stage buffer.
   u32x4 fr[12];
-  auto fetch = [&](const int st, const int half, const int natw, const int trw, const int j, const int set) __attribute__((always_inline)) {
-    const int pst = half == 0 ? st ^ 1 : st, ph = half ^ 1, u = j >> 1, db = 2 * (j & 1);
-    fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j] + (kv_nat(st, natw) + half * 8192)));
-    fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * ph + u] + (kv_tr(pst, trw) + db * 4096)));
-    fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j + 1] + (kv_nat(st, natw) + half * 8192)));
-    fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (ta[2 * ph + u] + (kv_tr(pst, trw) + (db + 1) * 4096)));
+  auto fetch = [&](const int st, const int half, const int j, const int set) __attribute__((always_inline)) {
+    const int pst = half == 0 ? (st + KV_BUFS - 1) % KV_BUFS : st, ph = half ^ 1, u = j >> 1, db = 2 * (j & 1);
+    const int po = kv_blk(pst, ph) + u * 4096;
+    fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j] + kv_blk(st, half)));
+    fr[set + 1] = tr_frag(tt[2 * db], tt[2 * db + 1], po);
+    fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j + 1] + kv_blk(st, half)));
+    fr[set + 3] = tr_frag(tt[2 * db + 2], tt[2 * db + 3], po);
   };
   auto frag = [&](const int idx) __attribute__((always_inline)) -> bf16x8 { return __builtin_bit_cast(bf16x8, fr[idx]); };
   // batches 0 and 1 must already be on their way into fr[0..3] and fr[4..7]; three sets rotate, two
-  // batches are in flight while one computes
+  // batches (six LDS reads each) are in flight while one computes
   // `chain` enters holding the bias words of its rows (load_bias, issued before the fragment fetches)
-  auto matrix_phase = [&](const int st, const int half, const int natw, const int trw, f32x16& chain,
-                          const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
+  auto matrix_phase = [&](const int st, const int half, f32x16& chain, const uint4& b0, const uint4& b1)
+      __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int set = 4 * (j % 3), db = 2 * (j & 1);
       if (j < 2) {
-        fetch(st, half, natw, trw, j + 2, 4 * ((j + 2) % 3));
-        __builtin_amdgcn_s_waitcnt(0xC87F);  // lgkmcnt(8): this batch has arrived
+        fetch(st, half, j + 2, 4 * ((j + 2) % 3));
+        __builtin_amdgcn_s_waitcnt(0xCC7F);  // lgkmcnt(12): this batch has arrived
       } else if (j == 2) {
-        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4)
+        __builtin_amdgcn_s_waitcnt(0xC67F);  // lgkmcnt(6)
       } else {
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
       }
@@ -279,25 +308,33 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
     }
   };
   // the transposed-tile product of the last block (it has no following step): 8 matrix instructions
-  auto flush_phase = [&](const int trw, const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
-    const bool st1 = ((s1 - s0 - 1) & 1) != 0;  // stage buffer of the last block
+  auto flush_phase = [&](const uint4& b0, const uint4& b1) __attribute__((always_inline)) {
+    const uint32_t last = (uint32_t)((n_st - 1) & (KV_BUFS - 1)) * 16384 + 8192;  // block 1 of the last stage's buffer
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const u32x4 f0 = *reinterpret_cast<const u32x4*>(smem + (ta[2 + u] + (kv_tr(0, trw) + k * 4096)));
-        const u32x4 f1 = *reinterpret_cast<const u32x4*>(smem + (ta[2 + u] + (kv_tr(1, trw) + k * 4096)));
-        fr[k] = st1 ? f1 : f0;
-      }
+      for (int k = 0; k < 4; ++k) fr[k] = tr_frag(tt[2 * k] + last, tt[2 * k + 1] + last, u * 4096);
 #pragma unroll
       for (int k = 0; k < 4; ++k) acc[k] = mfma32(frag(k), as_bf16x8(u == 0 ? b0 : b1), acc[k]);
     }
   };
 
-  // One loop iteration = one stage = two blocks, two barriers.  The next stage is copied in two parts
-  // (see above).  Role 0's matrix phase comes first in a step and its vector phase last; role 1 is the
-  // other way round, so the two waves of a SIMD keep both pipes busy.  Role 1 works one block behind
-  // role 0 (it needs the P of the block), and both add the transposed-tile product one step late.
+  // One call = one stage = two blocks, two barriers.  After the first barrier every wave has finished
+  // the previous stage's last block, so that stage's buffer takes the copy of the stage three ahead;
+  // before the second barrier the next stage must have landed (the copies of the two stages after it
+  // may still be in flight).  Role 0's matrix phase comes first in a step and its vector phase last;
+  // role 1 is the other way round, so the two waves of a SIMD keep both pipes busy.  Role 1 works one
+  // block behind role 0 (it needs the P of the block), and both add the transposed-tile product one
+  // step late.
+  auto stage_sync = [&](const int32_t s, const int st, auto&& second_step) __attribute__((always_inline)) {
+    __syncthreads();
+    const int32_t rs3 = real_next(rs2);
+    if (s + 3 < s1) copy_stage(rs3, (st + 3) % KV_BUFS);
+    second_step();
+    wait_stages((s + 2 < s1 ? 1 : 0) + (s + 3 < s1 ? 1 : 0));
+    __syncthreads();
+    rs = rs1; rs1 = rs2; rs2 = rs3;
+  };
   const int32_t tok_first = (int32_t)(first - first_q);
   // blocks below this index contain rows that do not see every key of the page (causal diagonal)
   const int32_t b_diag_end = tok_first + TP - 1 > 0 ? ((tok_first + TP - 1 + 31) / 32) * p.G : 0;
@@ -308,10 +345,9 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
       auto step0 = [&](const int st, const int half, const int32_t blk) __attribute__((always_inline)) {
         f32x16 sc;
         load_bias(st, half, sc);
-        // (no fetch ahead of the barrier: the transposed tiles of this stage may still be on their way)
-        fetch(st, half, 0, 1, 0, 0);
-        fetch(st, half, 0, 1, 1, 4);
-        matrix_phase(st, half, 0, 1, sc, p0, p1);
+        fetch(st, half, 0, 0);
+        fetch(st, half, 1, 4);
+        matrix_phase(st, half, sc, p0, p1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < 16; ++x) sc[x] = __builtin_amdgcn_exp2f(sc[x] * c);
@@ -326,23 +362,19 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         *reinterpret_cast<uint4*>(smem + (xo + half * 2048)) = p0;
         *reinterpret_cast<uint4*>(smem + (xo + (half * 2048 + 1024))) = p1;
       };
-      // s: stage counter; rs: its real stage; the next real stage is copied meanwhile
+      // s: stage counter; rs: its real stage
       auto stage0 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
-        const bool more = s + 1 < s1;
-        const int32_t rn = real_next(rs);
-        if (more) copy_natural(rn, st ^ 1);
-        step0(st, 0, 2 * rs);
-        mid_barrier(more);
-        if (more) copy_transposed(rn, st ^ 1);
-        step0(st, 1, 2 * rs + 1);
-        end_barrier();
-        rs = rn;
+        const int32_t blk = 2 * rs;
+        step0(st, 0, blk);
+        stage_sync(s, st, [&]() __attribute__((always_inline)) { step0(st, 1, blk + 1); });
       };
-      for (int32_t s = s0; s < s1; s += 2) {
+      for (int32_t s = s0; s < s1; s += 4) {
         stage0(s, 0);
         if (s + 1 < s1) stage0(s + 1, 1);
+        if (s + 2 < s1) stage0(s + 2, 2);
+        if (s + 3 < s1) stage0(s + 3, 3);
       }
-      flush_phase(1, p0, p1);
+      flush_phase(p0, p1);
     } else {
       // vector: dS = P o dP of the previous block;  matrix: dP = dO V^T - Delta  ||  dK^T += Q^T dS(previous block)
       auto step1 = [&](const int st, const int half, f32x16& dprev, f32x16& dcur) __attribute__((always_inline)) {
@@ -350,9 +382,9 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         load_bias(st, half, dcur);
         const uint4 p0 = *reinterpret_cast<const uint4*>(smem + (xo + ph * 2048));
         const uint4 p1 = *reinterpret_cast<const uint4*>(smem + (xo + (ph * 2048 + 1024)));
-        fetch(st, half, 1, 0, 0, 0);
-        fetch(st, half, 1, 0, 1, 4);
-        __builtin_amdgcn_s_waitcnt(0xC87F);  // lgkmcnt(8): P has arrived
+        fetch(st, half, 0, 0);
+        fetch(st, half, 1, 4);
+        __builtin_amdgcn_s_waitcnt(0xCC7F);  // lgkmcnt(12): P has arrived
         __builtin_amdgcn_sched_barrier(0);
         const uint32_t pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
 #pragma unroll
@@ -362,25 +394,20 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
         }
         const uint4 s0v = kv_pack8(dprev, 0), s1v = kv_pack8(dprev, 8);
         __builtin_amdgcn_sched_barrier(0);
-        matrix_phase(st, half, 1, 0, dcur, s0v, s1v);
+        matrix_phase(st, half, dcur, s0v, s1v);
       };
       f32x16 dpa, dpb;  // dP of even / odd blocks
 #pragma unroll
       for (int x = 0; x < 16; ++x) dpb[x] = 0.f;
       auto stage1 = [&](const int32_t s, const int st) __attribute__((always_inline)) {
-        const bool more = s + 1 < s1;
-        const int32_t rn = real_next(rs);
-        if (more) copy_natural(rn, st ^ 1);
         step1(st, 0, dpb, dpa);
-        mid_barrier(more);
-        if (more) copy_transposed(rn, st ^ 1);
-        step1(st, 1, dpa, dpb);
-        end_barrier();
-        rs = rn;
+        stage_sync(s, st, [&]() __attribute__((always_inline)) { step1(st, 1, dpa, dpb); });
       };
-      for (int32_t s = s0; s < s1; s += 2) {
+      for (int32_t s = s0; s < s1; s += 4) {
         stage1(s, 0);
         if (s + 1 < s1) stage1(s + 1, 1);
+        if (s + 2 < s1) stage1(s + 2, 2);
+        if (s + 3 < s1) stage1(s + 3, 3);
       }
       // the last block's dS and dK^T contribution
       {
@@ -393,7 +420,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
           dpb[2 * k + 1] *= __uint_as_float(pw[k] & 0xffff0000u);
         }
         const uint4 s0v = kv_pack8(dpb, 0), s1v = kv_pack8(dpb, 8);
-        flush_phase(0, s0v, s1v);
+        flush_phase(s0v, s1v);
       }
     }
   }

@@ -6,8 +6,8 @@
 //   bwd_prep   : Delta = <dO, O> and LSE * log2(e), both re-laid out in the KV head's
 //                "row space" r = 32 b + token-in-block (block b = tb * G + head in group)
 //                and padded to whole tiles.
-//   bwd_layout : row-space images of Q and dO (natural and transposed, swizzled) and
-//                the bias words of the dK/dV kernel, written once per call.
+//   bwd_layout : row-space images of Q and dO (swizzled LDS tiles) and the bias words of the
+//                dK/dV kernel, written once per call.
 //   bwd_dq     : parallel over 256-row tiles (like the forward); per 32-key block:
 //                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - Delta),
 //                dQ^T += K^T dS^T.  Every lane owns one query row.
@@ -295,50 +295,32 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
 
 // ---------------------------------------------------------------------------------
 // Row-space images of Q and dO for the dK/dV kernel.  Every (KV head, page) workgroup
-// of that kernel streams the same query rows; the LDS tiles it needs -- natural and
-// transposed, swizzled -- are laid out once here so that its staging is a plain copy.
-// Image of stage s (row-space blocks 2 s and 2 s + 1, 64 rows) of KV head g, 64 KiB:
-//   [0, 16K)   Q  natural:    row r, granule c (dims 8c..8c+7) at (r * 16 + (c ^ (r & 15))) * 16
-//   [16K, 32K) dO natural
-//   [32K, 48K) Q  transposed: row = dim d, granule o = 2u + hh holds rows 16u + 4hh + {0..3, 8..11};
-//                             at (d * 8 + (o ^ ((d >> 1) & 7))) * 16
-//   [48K, 64K) dO transposed
+// of that kernel streams the same query rows; the LDS tiles it needs are laid out once
+// here, already swizzled, so that its staging is a plain copy.
+// Image of stage s (row-space blocks 2 s and 2 s + 1, 64 rows) of KV head g, 32 KiB:
+//   [0, 16K)   Q:  row r, granule c (dims 8c..8c+7) at (r * 16 + (c ^ f(r))) * 16,
+//                  f(r) = 4 (r % 4) + (r / 4) % 4   (the swizzle under which both the row reads and
+//                  the transposing reads of that kernel are free of bank conflicts)
+//   [16K, 32K) dO, likewise
 // followed by the bias words of the stage: float [which][row], the per-row statistic (-LSE / c for
 // which = 0, -Delta for which = 1) from which the dK/dV kernel starts its accumulator chains.
-constexpr int IMG_BYTES = 65536;
+constexpr int IMG_BYTES = 32768;
 constexpr int IMG_STRIDE = IMG_BYTES + 512;
 
 __global__ __launch_bounds__(256) void bwd_layout_kernel(Params p, const float* __restrict__ delta_rs,
                                                          const float* __restrict__ lse2_rs, int64_t rows_pad,
                                                          unsigned char* __restrict__ img, int32_t n_stages) {
-  __shared__ __align__(16) unsigned char tile[64 * 256 + 64 * 16];  // 64 rows x 128 bf16, rows padded by 16 bytes
   const int s = blockIdx.x, which = blockIdx.y, g = blockIdx.z, tid = threadIdx.x;
   unsigned char* out = img + ((int64_t)g * n_stages + s) * IMG_STRIDE;
   const bf16_t* src = which == 0 ? (const bf16_t*)p.q : (const bf16_t*)p.d_o;
-  // natural rows -> padded LDS tile and natural image
 #pragma unroll
   for (int x = 0; x < 4; ++x) {
     const int gi = tid + 256 * x, r = gi >> 4, cg = gi & 15;
     const uint32_t blk = (uint32_t)(2 * s + (r >> 5)), tb = div_g(p, blk);
     const int i = (int)(32 * tb + (r & 31)), h = g * p.G + (int)(blk - tb * p.G);
     const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride + 8 * cg);
-    *reinterpret_cast<uint4*>(tile + r * 272 + cg * 16) = v;
-    *reinterpret_cast<uint4*>(out + which * 16384 + (r * 16 + (cg ^ (r & 15))) * 16) = v;
-  }
-  __syncthreads();
-  // transposed image: granule (d, o)
-#pragma unroll
-  for (int x = 0; x < 4; ++x) {
-    const int gi = tid + 256 * x, d = gi >> 3, o = gi & 7, u = o >> 1, h2 = o & 1;
-    uint32_t w[4];
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      const int r0 = 16 * u + 4 * h2 + ((2 * e2) & 3) + 8 * ((2 * e2) >> 2), r1 = r0 + 1;
-      const uint32_t lo = *reinterpret_cast<const unsigned short*>(tile + r0 * 272 + d * 2);
-      const uint32_t hi = *reinterpret_cast<const unsigned short*>(tile + r1 * 272 + d * 2);
-      w[e2] = lo | (hi << 16);
-    }
-    *reinterpret_cast<uint4*>(out + 32768 + which * 16384 + (d * 8 + (o ^ ((d >> 1) & 7))) * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    const int f = ((r & 3) << 2) | ((r >> 2) & 3);
+    *reinterpret_cast<uint4*>(out + which * 16384 + (r * 16 + (cg ^ f)) * 16) = v;
   }
   // bias words
   if (tid < 64) {

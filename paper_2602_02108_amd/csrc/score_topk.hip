@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(Params p, const float* 
   const T* base = (const T*)p.k_pool + (int64_t)p.page_table[lc] * p.pool_page_stride +
                   (int64_t)g * p.pool_head_stride + lr * VEC;
   float x[VEC];
-  seq_row_sum<T, 8, true>(base, p.pool_tok_stride, p.P, x);
+  seq_row_sum<T, 16, true>(base, p.pool_tok_stride, p.P, x);
   const float* qb = qbar + g * D + lr * VEC;
 #pragma unroll
   for (int v = 0; v < VEC; ++v) x[v] = __fmul_rn(qb[v], __fmul_rn(x[v], inv_p));
