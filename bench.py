@@ -551,10 +551,9 @@ def main():
     # per phase: algorithmic FLOPs over the summed kernel times of the phase
     def phase_ms(names):
         return sum(kernels[k]["avg_ms"] * kernels[k]["launches"] for k in names if k in kernels) / args.steps
-    # (kv_layout and qp_prepare run once per phase)
-    fwd_ms = phase_ms(["kv_layout", "qp_prepare", "attn_fwd_mfma"]) - 0.5 * phase_ms(["kv_layout", "qp_prepare"])
-    bwd_ms = phase_ms(["bwd_prep", "bwd_layout", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + \
-        0.5 * phase_ms(["kv_layout", "qp_prepare"])
+    # (kv_layout belongs to the forward; qp_prepare runs once per phase)
+    fwd_ms = phase_ms(["kv_layout", "qp_prepare", "attn_fwd_mfma"]) - 0.5 * phase_ms(["qp_prepare"])
+    bwd_ms = phase_ms(["bwd_prep", "bwd_dq_mfma", "bwd_dkv_mfma", "bwd_dkv_reduce"]) + 0.5 * phase_ms(["qp_prepare"])
     sel_ms = phase_ms(["qpool_partial", "qpool_final", "page_score", "page_score_cached", "topk_select", "page_means",
                        "kbar_image", "vote_lse", "vote_sum", "vote_finish"])
     phases = {"select_ms": sel_ms, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,

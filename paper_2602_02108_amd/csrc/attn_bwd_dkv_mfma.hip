@@ -18,8 +18,7 @@
 // rows, so the per-row statistics differ per register.  They are folded into the matrix
 // product: the accumulator chain of a block does not start from zero but from -LSE/c
 // (resp. -Delta) of the register's row, read from the stage's bias words (fp32, prepared
-// once, together with the swizzled Q / dO tile images, by a layout kernel) straight into
-// the accumulator registers.
+// once per call by the kernel that computes Delta) straight into the accumulator registers.
 //
 // LDS: four stage buffers of 64 query rows x {Q, dO} (16 KiB each, rows in natural order) + the
 // P exchange (4 pairs x 2 x 2 KiB) + bias words = 146 KiB.  Both products of a role read the same
@@ -74,7 +73,7 @@ template <> __device__ __forceinline__ void kv_rmw4<bf16_t>(bf16_t* ptr, float a
 // partial != nullptr: the unit's dK^T / dV^T go to partial[unit][2][128 keys][128 dims]
 // (fp32, overwritten) instead of the pool; a second kernel adds the slices to the pool.
 template <typename TG>
-__global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const unsigned char* __restrict__ img,
+__global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const float* __restrict__ bias,
                                                              int32_t n_stages, int32_t max_len, int32_t n_split,
                                                              int xcd_map, float* __restrict__ partial) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -161,61 +160,34 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 #pragma unroll
     for (int x = 0; x < 16; ++x) acc[db][x] = 0.f;
 
-  // LDS operand addresses: (lane base ^ constant) + immediate.  Granule c (dims 8c .. 8c+7) of row r
-  // of a 32-row block sits at granule position c ^ f(r), f(r) = 4 (r % 4) + (r / 4) % 4.
-  //  - chain operand (rows of the tile): lane (lq, hh) reads granule 2 kk + hh of row lq; 16
-  //    consecutive rows spread over all 16 positions.
-  //  - transposed operand: the lane must end up with column 32 db + lane % 32 of the rows
-  //    16 u + 8 r + 4 hh + {0..3} (read r = 0, 1), the order in which its partner's accumulator
-  //    registers hold the rows.  The transposing read returns to lane i of a group of 16 word i % 4
-  //    of the 8 bytes addressed by lanes i / 4 + {0, 4, 8, 12} of the group; so lane L of group gq
-  //    addresses row 16 u + 8 r + 4 (gq / 2) + L / 4, columns 32 db + 16 (gq % 2) + 4 (L % 4) .. + 3.
-  //    The 32 lanes served together touch 4 rows x 64 bytes, which f spreads over all banks.
+  // LDS operand addresses: (lane base ^ constant) + immediate.  Role 0 chains on Q rows and takes
+  // dO^T for its transposed-tile product, role 1 chains on dO rows and takes Q^T.
   uint32_t na[8], tt[8];
-  {
-    const uint32_t f = ((lq & 3) << 2) | ((lq >> 2) & 3);
-    const uint32_t nbase = lq * 256 + ((f ^ hh) << 4) + (role == 0 ? 0 : KV_DO);   // role 0 chains on Q, role 1 on dO
-#pragma unroll
-    for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
-    const uint32_t L = lane & 15, gq = lane >> 4;
-    const uint32_t trow = 4 * (gq >> 1) + (L >> 2);
-    const uint32_t tgran = (2 * (gq & 1) + ((L & 3) >> 1)) ^ (((L >> 2) << 2) | (gq >> 1));
-    const uint32_t tbase = trow * 256 + (tgran << 4) + 8 * (L & 1) + (role == 0 ? KV_DO : 0);  // role 0: dO^T, role 1: Q^T
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      tt[2 * db] = tbase ^ (db << 6);            // rows 16 u + 4 hh + {0..3}
-      tt[2 * db + 1] = tbase ^ (db << 6) ^ 32;   // rows 16 u + 8 + 4 hh + {0..3}: + 2048 as an immediate
-    }
-  }
+  row_tile_addrs(lq, hh, role == 0 ? 0 : KV_DO, na);
+  row_tile_tr_addrs(lane, role == 0 ? KV_DO : 0, tt);
   const uint32_t xo = KV_XCH + kbw * 4096 + lane * 16;  // this pair's P exchange, this lane's 16 bytes
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  // transposed fragment (dim block and read r folded into `addr`): eight 16-bit words of one column
-  auto tr_frag = [&](const uint32_t addr_r0, const uint32_t addr_r1, const int off) __attribute__((always_inline)) -> u32x4 {
-    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(smem + (addr_r0 + off))));
-    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4*)(smem + (addr_r1 + (off + 2048)))));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-  };
-  // Staging.  The query-side tiles of a stage (Q and dO, already swizzled) and its bias words are
-  // one contiguous image per (KV head, stage).  It is copied with direct global -> LDS loads (no
-  // staging registers, so several stages of copies can be in flight): every wave moves 4 KiB,
-  // waves 0 and 1 also the bias words.  This kernel orders the copies itself: they complete in
+  // Staging.  The query-side tiles of a stage are 2 x 32 rows of Q and of dO, each row 256 contiguous
+  // bytes of the chunk's tensors; they are copied with direct global -> LDS loads (no staging
+  // registers, so several stages of copies can be in flight; the swizzle is applied on the source
+  // side): every wave moves 16 rows (4 KiB) -- waves 0..3 those of Q, 4..7 those of dO -- and waves
+  // 0 and 1 also the stage's bias words.  This kernel orders the copies itself: they complete in
   // issue order, so "at most n outstanding" before a barrier publishes everything older than the
   // newest n.
-  constexpr int IMG_BYTES = 32768, IMG_STRIDE = IMG_BYTES + 512;
-  const unsigned char* img_g = img + (int64_t)g * n_stages * IMG_STRIDE;
-  const uint32_t cp_off = 4096 * wave + 16 * lane;  // lane offset inside an image
+  uint32_t cp_rows[4];
+  row_tile_src_offsets16(lane, (uint32_t)(p.q_tok_stride * 2), cp_rows);
+  const unsigned char* cp_src = (const unsigned char*)(wave < 4 ? p.q : p.d_o);
+  const float* bias_g = bias + (int64_t)g * n_stages * 128;
   const uint32_t cp_bias = 256 * wave + 4 * lane;   // (waves 0, 1) lane offset inside the bias words
-  const uint32_t cp_dst = (wave >> 2) * KV_DO + (wave & 3) * 4096;   // waves 0..3 move Q, 4..7 dO
+  const uint32_t cp_dst = (wave >> 2) * KV_DO + (wave & 3) * 4096;
   // stage s -> stage buffer st.  The buffer's last readers must have passed a barrier.
   auto copy_stage = [&](const int32_t s, const int st) __attribute__((always_inline)) {
-    const unsigned char* base = img_g + (int64_t)s * IMG_STRIDE;
-    copy_kib_to_lds<4>(base, cp_off, st * 16384 + cp_dst);
-    if (wave < 2) copy_256b_to_lds(base + IMG_BYTES, cp_bias, KV_BIAS + st * 512 + 256 * wave);
+    const uint32_t blk = (uint32_t)(2 * s + ((wave & 3) >> 1)), tb = div_g(p, blk);   // this wave's block: one head, 32 tokens
+    const int64_t row0 = (int64_t)(32 * tb + 16 * (wave & 1)) * p.q_tok_stride +
+                         (int64_t)(g * p.G + (int)(blk - tb * p.G)) * p.q_head_stride;
+    copy_rows16_to_lds(cp_src + row0 * 2, cp_rows, st * 16384 + cp_dst);
+    if (wave < 2) copy_256b_to_lds((const unsigned char*)(bias_g + (int64_t)s * 128), cp_bias, KV_BIAS + st * 512 + 256 * wave);
   };
   // all but the newest n stages of copies have landed (a stage is 4 loads, 5 for waves 0 and 1)
   auto wait_stages = [&](const int n) __attribute__((always_inline)) {
@@ -277,9 +249,9 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
     const int pst = half == 0 ? (st + KV_BUFS - 1) % KV_BUFS : st, ph = half ^ 1, u = j >> 1, db = 2 * (j & 1);
     const int po = kv_blk(pst, ph) + u * 4096;
     fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j] + kv_blk(st, half)));
-    fr[set + 1] = tr_frag(tt[2 * db], tt[2 * db + 1], po);
+    fr[set + 1] = row_tile_tr_frag(smem, tt[2 * db], tt[2 * db + 1], po);
     fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * j + 1] + kv_blk(st, half)));
-    fr[set + 3] = tr_frag(tt[2 * db + 2], tt[2 * db + 3], po);
+    fr[set + 3] = row_tile_tr_frag(smem, tt[2 * db + 2], tt[2 * db + 3], po);
   };
   auto frag = [&](const int idx) __attribute__((always_inline)) -> bf16x8 { return __builtin_bit_cast(bf16x8, fr[idx]); };
   // batches 0 and 1 must already be on their way into fr[0..3] and fr[4..7]; three sets rotate, two
@@ -313,7 +285,7 @@ __global__ __launch_bounds__(KV_THREADS) void bwd_dkv_kernel(Params p, const uns
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) fr[k] = tr_frag(tt[2 * k] + last, tt[2 * k + 1] + last, u * 4096);
+      for (int k = 0; k < 4; ++k) fr[k] = row_tile_tr_frag(smem, tt[2 * k] + last, tt[2 * k + 1] + last, u * 4096);
 #pragma unroll
       for (int k = 0; k < 4; ++k) acc[k] = mfma32(frag(k), as_bf16x8(u == 0 ? b0 : b1), acc[k]);
     }
@@ -500,7 +472,7 @@ int32_t dkv_splits(const Params& p, int32_t max_len) {
   return (int32_t)(want < 1 ? 1 : (want > 4 ? 4 : want));
 }
 
-hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
+hipError_t launch_bwd_dkv_mfma(const Params& p, const float* bias, int32_t n_stages, int32_t max_len,
                                float* partial_ws, hipStream_t st) {
   static DeviceOnce lds_once_f32, lds_once_bf16;
   if (hipError_t e = ensure_max_dynamic_lds(lds_once_f32, (const void*)bwd_dkv_kernel<float>, KV_LDS); e != hipSuccess) return e;
@@ -515,10 +487,10 @@ hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_
   {
     ProfScope prof_("bwd_dkv_mfma", st);
     if (p.grad_is_bf16)
-      bwd_dkv_kernel<bf16_t><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, img, n_stages, max_len, n_split, xcd_map,
+      bwd_dkv_kernel<bf16_t><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, bias, n_stages, max_len, n_split, xcd_map,
                                                                               partial);
     else
-      bwd_dkv_kernel<float><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, img, n_stages, max_len, n_split, xcd_map,
+      bwd_dkv_kernel<float><<<dim3(blocks), dim3(KV_THREADS), KV_LDS, st>>>(p, bias, n_stages, max_len, n_split, xcd_map,
                                                                              partial);
   }
   hipError_t e = hipGetLastError();

@@ -5,12 +5,13 @@
 // Kernels:
 //   bwd_prep   : Delta = <dO, O> and LSE * log2(e), both re-laid out in the KV head's
 //                "row space" r = 32 b + token-in-block (block b = tb * G + head in group)
-//                and padded to whole tiles.
-//   bwd_layout : row-space images of Q and dO (swizzled LDS tiles) and the bias words of the
-//                dK/dV kernel, written once per call.
+//                and padded to whole tiles; and the bias words of the dK/dV kernel: per
+//                64-row stage float [which][row], -LSE / c for which = 0 and -Delta for
+//                which = 1, from which that kernel starts its accumulator chains.
 //   bwd_dq     : parallel over 256-row tiles (like the forward); per 32-key block:
 //                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - Delta),
-//                dQ^T += K^T dS^T.  Every lane owns one query row.
+//                dQ^T += K^T dS^T.  Every lane owns one query row.  K and V half tiles come
+//                straight from the paged pools.
 //   bwd_dkv    : (attn_bwd_dkv_mfma.hip) one workgroup OWNS one (KV head, selected page).
 #include "mfma_common.h"
 #include "launch.h"
@@ -39,7 +40,8 @@ static inline int64_t rows_padded(const Params& p) {
 // ---------------------------------------------------------------------------------
 // 16 lanes per row (8 elements each), 4 rows per wave.
 __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restrict__ delta_rs,
-                                                       float* __restrict__ lse2_rs, int64_t rows_pad) {
+                                                       float* __restrict__ lse2_rs, int64_t rows_pad,
+                                                       float* __restrict__ bias, int32_t n_stages) {
   const int lane16 = threadIdx.x & 15;
   const int64_t idx = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);  // over Hkv * rows_pad
   if (idx >= (int64_t)p.Hkv * rows_pad) return;
@@ -67,23 +69,25 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(Params p, float* __restri
   if (lane16 == 0) {
     delta_rs[idx] = acc;
     lse2_rs[idx] = l2;
+    if (r < rows_total) {
+      float* b = bias + (((int64_t)g * n_stages + (r >> 6)) * 2) * 64 + (r & 63);
+      b[0] = -l2 / (p.sm_scale * 1.4426950408889634f);
+      b[64] = -acc;
+    }
   }
 }
 
 // ---------------------------------------------------------------------------------
-// dQ.  LDS: two stages of {K natural half tile, V natural half tile, K transposed
-// half tile}, 16 KiB each.  One barrier per half tile of 64 keys; the next half tile
-// is copied from the pre-laid-out images into the other stage with direct global ->
-// LDS loads while the current one is consumed.  The natural tiles of both stages sit
-// in the lower 64 KiB and the transposed tiles above them, so that every operand
-// address is a loop-invariant register plus an immediate offset.
-constexpr int DQ_LDS = 6 * 16384;
-constexpr int DQ_KT = 4 * 16384;  // first transposed tile
+// dQ.  LDS: two stages of {K half tile, V half tile} (64 keys x 128 dims, 16 KiB each, row tiles).
+// One barrier per half tile of 64 keys; the next half tile is copied straight from the paged pools
+// into the other stage with direct global -> LDS loads while the current one is consumed (the
+// swizzle is applied on the source side, so no re-laid-out copy of the pages is needed).  K^T for
+// the dQ product is read from the K tile with the transposing LDS read.
+constexpr int DQ_LDS = 4 * 16384;
 
 __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const float* __restrict__ delta_rs,
                                                             const float* __restrict__ lse2_rs, int64_t rows_pad,
-                                                            int tiles_per_head, int xcd_map,
-                                                            const unsigned char* __restrict__ kv_img, int32_t img_len) {
+                                                            int tiles_per_head, int xcd_map) {
   extern __shared__ __align__(16) unsigned char smem[];
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5, lq = lane & 31;
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
 
   const int32_t T = visible_len(p, lid, a_blk_max / TP, lane);
   PageWindow pw;
-  pw.init(p, lid, T, lane);
+  pw.init(p, lid, T, lane, false);
   int32_t T2 = 2 * T;
   if (T > 0 && (int64_t)list_at(p, lid, T - 1) * TP + 64 > a_blk_max) T2 -= 1;  // second half of the last page unseen
   // half tiles [0, T_full) are seen in full by every row of the workgroup
@@ -144,36 +148,21 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
     for (int x = 0; x < 16; ++x) dq[db][x] = 0.f;
 
   // LDS operand addresses: (lane base ^ constant) + immediate
-  uint32_t na[8], ta[4];
-  {
-    const uint32_t nbase = lq * 256 + (((lq & 15) ^ hh) << 4);          // natural tiles, 16 granules per row
-    const uint32_t tbase = lq * 128 + ((((lq >> 1) & 7) ^ hh) << 4);    // transposed tile, 8 granules per row
-#pragma unroll
-    for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) ta[k] = (tbase ^ (k << 5)) + DQ_KT;
-  }
+  uint32_t na[8], tt[8];
+  row_tile_addrs(lq, hh, 0, na);
+  row_tile_tr_addrs(lane, 0, tt);
 
-  // Staging.  The K natural, V natural and K transposed half tiles come from images that already have
-  // the byte order of the LDS tiles (one 16 KiB image per kind, KV head and half tile of the page
-  // list), so a stage is copied with direct global -> LDS loads: no staging registers, no LDS store
-  // instructions.  The kernel waits for them itself before the barrier that publishes the stage.
-  // Wave w moves bytes 2048 w .. + 2047 of each image.
-  const size_t kind_bytes = (size_t)p.Hkv * img_len * 16384;
-  const unsigned char* const kn_img = kv_img + (size_t)g * img_len * 16384;
-  const unsigned char* const vn_img = kn_img + kind_bytes;
-  const unsigned char* const kt_img = vn_img + kind_bytes;
-  const uint32_t cp_off = 2048 * wave + 16 * lane;
-  auto copy_tile = [&](const unsigned char* src, const uint32_t lds_dst) __attribute__((always_inline)) {
-    copy_kib_to_lds<2>(src, cp_off, lds_dst + 2048 * wave);
-  };
-  // (image index of a half tile: its list position, or with one list per query page the page's
-  // position in the KV head's union list)
+  // Staging.  A half tile of K (and of V) is 64 consecutive tokens of one page and KV head in the
+  // pool; wave w moves its rows 8 w .. 8 w + 7 (2 KiB of the LDS tile) with two direct global -> LDS
+  // loads per tile: no staging registers, no LDS store instructions.  The kernel waits for them
+  // itself before the barrier that publishes the stage.
+  uint32_t cp0, cp1;
+  row_tile_src_offsets(8 * wave, lane, (uint32_t)(p.pool_tok_stride * 2), cp0, cp1);
+  const int64_t head_off = (int64_t)g * p.pool_head_stride;
   auto copy_stage = [&](const int32_t ht, const int st) __attribute__((always_inline)) {
-    const size_t o = (size_t)(p.qp ? 2 * pw.phys(ht >> 1) + (ht & 1) : ht) * 16384;
-    copy_tile(kn_img + o, st * 32768);
-    copy_tile(vn_img + o, st * 32768 + 16384);
-    copy_tile(kt_img + o, DQ_KT + st * 16384);
+    const int64_t o = ((int64_t)pw.phys(ht >> 1) * p.pool_page_stride + head_off + (int64_t)(ht & 1) * 64 * p.pool_tok_stride) * 2;
+    copy_rows_to_lds((const unsigned char*)p.k_pool + o, cp0, cp1, st * 32768 + 2048 * wave);
+    copy_rows_to_lds((const unsigned char*)p.v_pool + o, cp0, cp1, st * 32768 + 16384 + 2048 * wave);
   };
   auto copies_landed = [&]() __attribute__((always_inline)) { wait_copies<0>(); };
   auto ht_first = [&](int32_t ht) -> int64_t { return (int64_t)pw.page(ht >> 1) * TP + (ht & 1) * 64; };
@@ -181,25 +170,25 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   // One half tile is 12 batches of four matrix instructions.  Per 32-key block kb2: four batches
   // compute S^T and dP^T (fragments: K rows and V rows of k-steps 2b, 2b+1, used alternately so
   // that neighbouring instructions are independent), the vector unit turns them into dS^T, and two
-  // batches add K^T dS^T of the block to dQ^T (dim blocks 0,1 then 2,3).  The fragments of a batch
-  // are fetched while the previous batch computes; one wait per batch.
+  // batches add K^T dS^T of the block to dQ^T (dim blocks 0,1 then 2,3; transposing reads of the K
+  // tile, two per fragment).  The fragments of a batch are fetched while the previous batch
+  // computes; one wait per batch.
   u32x4 fr[8];
   bf16x8 dsf[2];
   auto fetch = [&](const int st, const int n, const int set) __attribute__((always_inline)) {
     const int kb2 = n / 6, b = n % 6;
+    const int o = st * 32768 + kb2 * 8192;
     if (b < 4) {
-      const int o = st * 32768 + kb2 * 8192;
       fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b] + o));
       fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b] + (o + 16384)));
       fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b + 1] + o));
       fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (na[2 * b + 1] + (o + 16384)));
     } else {
-      const int db = 2 * (b - 4), u = 2 * kb2;
-      const int o = st * 16384;
-      fr[set + 0] = *reinterpret_cast<const u32x4*>(smem + (ta[u] + (o + 4096 * db)));
-      fr[set + 1] = *reinterpret_cast<const u32x4*>(smem + (ta[u] + (o + 4096 * (db + 1))));
-      fr[set + 2] = *reinterpret_cast<const u32x4*>(smem + (ta[u + 1] + (o + 4096 * db)));
-      fr[set + 3] = *reinterpret_cast<const u32x4*>(smem + (ta[u + 1] + (o + 4096 * (db + 1))));
+      const int db = 2 * (b - 4);
+      fr[set + 0] = row_tile_tr_frag(smem, tt[2 * db], tt[2 * db + 1], o);
+      fr[set + 1] = row_tile_tr_frag(smem, tt[2 * db + 2], tt[2 * db + 3], o);
+      fr[set + 2] = row_tile_tr_frag(smem, tt[2 * db], tt[2 * db + 1], o + 4096);
+      fr[set + 3] = row_tile_tr_frag(smem, tt[2 * db + 2], tt[2 * db + 3], o + 4096);
     }
   };
   auto half_tile = [&](const int st, const bool general, const int rel) __attribute__((always_inline)) {
@@ -211,7 +200,9 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
       const int kb2 = n / 6, b = n % 6;
       if (n + 1 < 12) {
         fetch(st, n + 1, 4 - set);
-        __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4): this batch has arrived
+        // this batch has arrived: only the reads of the next one (4 row reads or 8 transposing reads) are out
+        if ((n + 1) % 6 < 4) __builtin_amdgcn_s_waitcnt(0xC47F);  // lgkmcnt(4)
+        else __builtin_amdgcn_s_waitcnt(0xC87F);                  // lgkmcnt(8)
         __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of this batch's matrix instructions
       }
       if (b < 4) {
@@ -293,55 +284,14 @@ __global__ __launch_bounds__(BW_THREADS) void bwd_dq_kernel(Params p, const floa
   }
 }
 
-// ---------------------------------------------------------------------------------
-// Row-space images of Q and dO for the dK/dV kernel.  Every (KV head, page) workgroup
-// of that kernel streams the same query rows; the LDS tiles it needs are laid out once
-// here, already swizzled, so that its staging is a plain copy.
-// Image of stage s (row-space blocks 2 s and 2 s + 1, 64 rows) of KV head g, 32 KiB:
-//   [0, 16K)   Q:  row r, granule c (dims 8c..8c+7) at (r * 16 + (c ^ f(r))) * 16,
-//                  f(r) = 4 (r % 4) + (r / 4) % 4   (the swizzle under which both the row reads and
-//                  the transposing reads of that kernel are free of bank conflicts)
-//   [16K, 32K) dO, likewise
-// followed by the bias words of the stage: float [which][row], the per-row statistic (-LSE / c for
-// which = 0, -Delta for which = 1) from which the dK/dV kernel starts its accumulator chains.
-constexpr int IMG_BYTES = 32768;
-constexpr int IMG_STRIDE = IMG_BYTES + 512;
-
-__global__ __launch_bounds__(256) void bwd_layout_kernel(Params p, const float* __restrict__ delta_rs,
-                                                         const float* __restrict__ lse2_rs, int64_t rows_pad,
-                                                         unsigned char* __restrict__ img, int32_t n_stages) {
-  const int s = blockIdx.x, which = blockIdx.y, g = blockIdx.z, tid = threadIdx.x;
-  unsigned char* out = img + ((int64_t)g * n_stages + s) * IMG_STRIDE;
-  const bf16_t* src = which == 0 ? (const bf16_t*)p.q : (const bf16_t*)p.d_o;
-#pragma unroll
-  for (int x = 0; x < 4; ++x) {
-    const int gi = tid + 256 * x, r = gi >> 4, cg = gi & 15;
-    const uint32_t blk = (uint32_t)(2 * s + (r >> 5)), tb = div_g(p, blk);
-    const int i = (int)(32 * tb + (r & 31)), h = g * p.G + (int)(blk - tb * p.G);
-    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)i * p.q_tok_stride + (int64_t)h * p.q_head_stride + 8 * cg);
-    const int f = ((r & 3) << 2) | ((r >> 2) & 3);
-    *reinterpret_cast<uint4*>(out + which * 16384 + (r * 16 + (cg ^ f)) * 16) = v;
-  }
-  // bias words
-  if (tid < 64) {
-    const float c = p.sm_scale * 1.4426950408889634f;
-    const int64_t ri = (int64_t)g * rows_pad + (int64_t)64 * s + tid;
-    const float v = which == 0 ? -lse2_rs[ri] / c : -delta_rs[ri];
-    reinterpret_cast<float*>(out + IMG_BYTES)[which * 64 + tid] = v;
-  }
-}
-
 static inline size_t stats_bytes(const Params& p) {
   return (2 * (size_t)p.Hkv * (size_t)rows_padded(p) * sizeof(float) + 255) & ~(size_t)255;
 }
-static inline int32_t img_stages(const Params& p) { return (p.C / 32) * p.G / 2; }
-static inline size_t img_bytes(const Params& p) { return (size_t)p.Hkv * (size_t)img_stages(p) * IMG_STRIDE; }
-
-constexpr int DQ_IMG_KINDS = 1 | 2 | 4;  // K natural, V natural, K transposed
+static inline int32_t row_stages(const Params& p) { return (p.C / 32) * p.G / 2; }   // 64-row stages of the dK/dV kernel
+static inline size_t bias_bytes(const Params& p) { return (size_t)p.Hkv * (size_t)row_stages(p) * 512; }
 
 size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
-  return stats_bytes(p) + img_bytes(p) + kv_image_bytes(p, max_list_len, DQ_IMG_KINDS) +
-         dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
+  return stats_bytes(p) + bias_bytes(p) + dkv_partial_bytes(p, max_list_len, dkv_splits(p, max_list_len));
 }
 
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
@@ -350,33 +300,24 @@ hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   const int64_t rows_pad = rows_padded(p);
   float* delta_rs = (float*)ws;
   float* lse2_rs = delta_rs + (size_t)p.Hkv * rows_pad;
-  unsigned char* img = (unsigned char*)ws + stats_bytes(p);  // row-space images of Q / dO
-  unsigned char* kv_img = img + img_bytes(p);                // images of the selected K / V pages
+  float* bias = (float*)((unsigned char*)ws + stats_bytes(p));   // bias words of the dK/dV kernel
   {
     const int64_t total = (int64_t)p.Hkv * rows_pad;
     ProfScope prof_("bwd_prep", st);
-    bwd_prep_kernel<<<dim3((unsigned)((total + 15) / 16)), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad);
+    bwd_prep_kernel<<<dim3((unsigned)((total + 15) / 16)), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad, bias,
+                                                                               row_stages(p));
   }
   const int xcd_map = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 1 : 0;
   const int per = xcd_map ? 8 / p.Hkv : 1;
   {
     const int tiles = row_tiles_per_head(p.C, p.G, p.m, p.qp);
     const unsigned blocks = xcd_map ? 8u * (unsigned)((tiles + per - 1) / per) : (unsigned)tiles * p.Hkv;
-    hipError_t e = launch_kv_layout(p, max_list_len, DQ_IMG_KINDS, kv_img, st);
-    if (e != hipSuccess) return e;
     ProfScope prof_("bwd_dq_mfma", st);
-    bwd_dq_kernel<<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map, kv_img,
-                                                                   2 * max_list_len);
-  }
-  {
-    ProfScope prof_("bwd_layout", st);
-    bwd_layout_kernel<<<dim3((unsigned)img_stages(p), 2, (unsigned)p.Hkv), dim3(256), 0, st>>>(p, delta_rs, lse2_rs, rows_pad, img,
-                                                                                              img_stages(p));
+    bwd_dq_kernel<<<dim3(blocks), dim3(BW_THREADS), DQ_LDS, st>>>(p, delta_rs, lse2_rs, rows_pad, tiles, xcd_map);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_bwd_dkv_mfma(p, img, img_stages(p), max_list_len,
-                             (float*)(kv_img + kv_image_bytes(p, max_list_len, DQ_IMG_KINDS)), st);
+  return launch_bwd_dkv_mfma(p, bias, row_stages(p), max_list_len, (float*)((unsigned char*)bias + bias_bytes(p)), st);
 }
 
 }  // namespace oomb

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
   // number of half tiles visible to this workgroup (lists are ascending)
   const int32_t T = visible_len(p, lid, a_blk_max / TP, lane);
   PageWindow pw;
-  pw.init(p, lid, T, lane);
+  pw.init(p, lid, T, lane, p.qp != 0);
   int32_t T2 = 2 * T;
   if (T > 0 && (int64_t)list_at(p, lid, T - 1) * TP + HT > a_blk_max) T2 -= 1;  // second half of the last page unseen
 
@@ -318,7 +318,8 @@ __global__ __launch_bounds__(FW_THREADS) void fwd_mfma_kernel(Params p, int tile
 }
 
 bool mfma_supported(const Params& p, bool is_bf16) {
-  return is_bf16 && p.D == HD && p.P == TP;
+  // (token strides: the direct copies of the backward kernels address the rows of a tile with a 32-bit lane offset)
+  return is_bf16 && p.D == HD && p.P == TP && p.pool_tok_stride <= (1 << 20) && p.q_tok_stride <= (1 << 20);
 }
 
 constexpr int FW_IMG_KINDS = 1 | 8;  // K natural, V transposed

@@ -51,7 +51,7 @@ size_t bwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len);
 hipError_t launch_bwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st);
 size_t dkv_partial_bytes(const Params& p, int32_t max_len, int32_t n_split);
 int32_t dkv_splits(const Params& p, int32_t max_len);
-hipError_t launch_bwd_dkv_mfma(const Params& p, const unsigned char* img, int32_t n_stages, int32_t max_len,
+hipError_t launch_bwd_dkv_mfma(const Params& p, const float* bias, int32_t n_stages, int32_t max_len,
                                float* partial_ws, hipStream_t st);
 
 // offload.hip: staging plan and transfers between pinned host pools and device staging pools

@@ -6,18 +6,28 @@
 //   B operand: lane l holds B[8 * (l / 32) + 0..7][l % 32]
 //   C/D:       lane l, register r holds C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32]
 //
-// LDS tiles: natural rows are 256 bytes (16 granules of 16 bytes), granule c of
-// row r stored at granule position c ^ (r & 15); transposed rows are 128 bytes
-// (8 granules), granule o of row d stored at o ^ ((d >> 1) & 7).  Both make the
-// row-per-lane 16-byte operand reads free of bank conflicts.  The tiles are
-// written in this byte order once per call by the layout kernels ("images") and
-// copied into LDS verbatim.
+// LDS tiles of the forward kernel (written in this byte order once per call by a layout
+// kernel, "images", and copied into LDS verbatim): natural rows are 256 bytes (16 granules of
+// 16 bytes), granule c of row r stored at granule position c ^ (r & 15); transposed rows are
+// 128 bytes (8 granules), granule o of row d stored at o ^ ((d >> 1) & 7).  Both make the
+// row-per-lane 16-byte operand reads free of bank conflicts.
 //   "natural" tile:    row = token, granule c = elements 8c .. 8c+7 of the head dim.
 //   "transposed" tile: row = head-dim index d; granule o = 2 * u + hh holds the
 //                      eight tokens 16u + 4hh + {0,1,2,3, 8,9,10,11}; this is the
 //                      token order in which a lane of C-layout half hh holds the
 //                      rows of a 32x32 accumulator block, so a probability block
 //                      can feed the next MFMA without any cross-lane movement.
+//
+// LDS tiles of the backward kernels ("row tiles"): rows in natural order, 256 bytes each, granule c
+// of row r at granule position c ^ f(r), f(r) = 4 (r % 4) + (r / 4) % 4.  Such a tile serves both
+// as an operand whose contraction runs along the row (16-byte row reads; 16 consecutive rows use all
+// 16 positions) and as the transposed operand, fetched with ds_read_b64_tr_b16: lane i of a group of
+// 16 receives word i % 4 of the 8 bytes addressed by lanes i / 4 + {0, 4, 8, 12} of its group.  With
+// lane L of group gq (= lane / 16) addressing row 16 u + 8 r + 4 (gq / 2) + L / 4, columns
+// 32 db + 16 (gq % 2) + 4 (L % 4) .. + 3, the lane ends up with column 32 db + lane % 32 of the rows
+// 16 u + 8 r + 4 (lane / 32) + {0..3}; reads r = 0, 1 together are the eight contraction elements in
+// the order of the accumulator rows (see "transposed" above).  The 32 lanes served together touch
+// 4 rows x 64 bytes, which f spreads over all banks.
 #pragma once
 #include "common.h"
 
@@ -88,6 +98,83 @@ template <int N> __device__ __forceinline__ void wait_copies() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | N);
 }
 
+// ---- row tiles: operand addresses and the transposing read -------------------------------
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ constexpr uint32_t row_tile_f(uint32_t r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// byte offset of granule c of row r inside a row tile
+__device__ __forceinline__ constexpr uint32_t row_tile_at(uint32_t r, uint32_t c) { return r * 256 + ((c ^ row_tile_f(r)) << 4); }
+
+// row operand of lane (lq = lane % 32, hh = lane / 32), k-step kk (dims 16 kk + 8 hh .. + 7) of a 32-row
+// block: na[kk] + block offset
+__device__ __forceinline__ void row_tile_addrs(int lq, int hh, uint32_t base, uint32_t (&na)[8]) {
+  const uint32_t nbase = lq * 256 + ((row_tile_f(lq) ^ hh) << 4) + base;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) na[k] = nbase ^ (k << 5);
+}
+// transposed operand: dim block db, rows 16 u + 8 r + ...: tt[2 db + r] + 4096 u + 2048 r + block offset
+__device__ __forceinline__ void row_tile_tr_addrs(int lane, uint32_t base, uint32_t (&tt)[8]) {
+  const uint32_t L = lane & 15, gq = lane >> 4;
+  const uint32_t trow = 4 * (gq >> 1) + (L >> 2);
+  const uint32_t tgran = (2 * (gq & 1) + ((L & 3) >> 1)) ^ (((L >> 2) << 2) | (gq >> 1));
+  const uint32_t tbase = trow * 256 + (tgran << 4) + 8 * (L & 1) + base;
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    tt[2 * db] = tbase ^ (db << 6);
+    tt[2 * db + 1] = tbase ^ (db << 6) ^ 32;   // rows + 8: f changes by 2
+  }
+}
+// eight 16-bit words of one column: the reads r = 0 (address a0 + off) and r = 1 (a1 + off + 2048)
+__device__ __forceinline__ u32x4_t row_tile_tr_frag(const unsigned char* smem, uint32_t a0, uint32_t a1, int off) {
+  const u32x2_t lo = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4_t*)(smem + (a0 + off))));
+  const u32x2_t hi = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4_t*)(smem + (a1 + (off + 2048)))));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+}
+
+// Direct copy of 2 KiB (8 rows) of a row tile whose rows lie `row_bytes` apart in memory: the swizzle
+// is applied on the source side (every lane picks the granule that belongs at its LDS position).
+// off0 / off1: this lane's source offsets for the two KiB (row_tile_src_offsets); the second load
+// carries an immediate of 1024 for the LDS side, which off1 compensates.
+__device__ __forceinline__ void row_tile_src_offsets(int first_row, int lane, uint32_t row_bytes, uint32_t& off0, uint32_t& off1) {
+  const uint32_t pos = lane & 15;
+  const uint32_t r0 = first_row + (lane >> 4), r1 = r0 + 4;
+  off0 = r0 * row_bytes + ((pos ^ row_tile_f(r0)) << 4);
+  off1 = r1 * row_bytes + ((pos ^ row_tile_f(r1)) << 4) - 1024;
+}
+__device__ __forceinline__ void copy_rows_to_lds(const unsigned char* src, uint32_t off0, uint32_t off1, uint32_t lds_dst) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %3\n\t"
+      "global_load_lds_dwordx4 %2, %3 offset:1024\n\t"
+      :: "s"(lds_dst), "v"(off0), "v"(off1), "s"(src) : "memory", "m0");
+}
+
+// 4 KiB (16 rows): four loads, lane offsets from row_tile_src_offsets16
+__device__ __forceinline__ void row_tile_src_offsets16(int lane, uint32_t row_bytes, uint32_t (&off)[4]) {
+  const uint32_t pos = lane & 15;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t r = 4 * k + (lane >> 4);   // (first row a multiple of 16: f only sees r % 16)
+    off[k] = r * row_bytes + ((pos ^ row_tile_f(r)) << 4) - 1024 * k;
+  }
+}
+__device__ __forceinline__ void copy_rows16_to_lds(const unsigned char* src, const uint32_t (&off)[4], uint32_t lds_dst) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %5\n\t"
+      "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+      "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+      "global_load_lds_dwordx4 %4, %5 offset:3072\n\t"
+      :: "s"(lds_dst), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(src) : "memory", "m0");
+}
+
 // Page list entries held in registers, 64 per window, two windows deep: lane j of a
 // window holds the logical page id of list entry base + j and, in `ph`, its physical
 // page -- or, with one list per query page, the position of the page in the KV head's
@@ -98,18 +185,20 @@ template <int N> __device__ __forceinline__ void wait_copies() {
 struct PageWindow {
   int32_t l_cur, p_cur, l_nxt, p_nxt;
   int32_t base;
-  static __device__ __forceinline__ void fetch(const Params& p, int lid, int32_t len, int32_t b, int lane,
-                                               int32_t& l, int32_t& ph) {
+  bool slots;  // (one list per query page) ph = position in the union list instead of the physical page
+  __device__ __forceinline__ void fetch(const Params& p, int lid, int32_t len, int32_t b, int lane,
+                                        int32_t& l, int32_t& ph) const {
     const int32_t j = b + lane;
     l = 0;
     ph = 0;
     if (j < len) {
       l = list_at(p, lid, j);
-      ph = p.qp ? p.qp_slot[(int64_t)lid * p.sel_stride + j] : p.page_table[l];
+      ph = slots ? p.qp_slot[(int64_t)lid * p.sel_stride + j] : p.page_table[l];
     }
   }
-  __device__ __forceinline__ void init(const Params& p, int lid, int32_t len, int lane) {
+  __device__ __forceinline__ void init(const Params& p, int lid, int32_t len, int lane, bool want_slots) {
     base = 0;
+    slots = want_slots;
     fetch(p, lid, len, 0, lane, l_cur, p_cur);
     fetch(p, lid, len, 64, lane, l_nxt, p_nxt);
   }
