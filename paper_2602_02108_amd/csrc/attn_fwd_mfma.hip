@@ -322,10 +322,8 @@ bool mfma_supported(const Params& p, bool is_bf16) {
   return is_bf16 && p.D == HD && p.P == TP && p.pool_tok_stride <= (1 << 20) && p.q_tok_stride <= (1 << 20);
 }
 
-constexpr int FW_IMG_KINDS = 1 | 8;  // K natural, V transposed
-
 size_t fwd_mfma_workspace_bytes(const Params& p, int32_t max_list_len) {
-  return kv_image_bytes(p, max_list_len, FW_IMG_KINDS);
+  return kv_image_bytes(p, max_list_len);
 }
 
 hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipStream_t st) {
@@ -340,10 +338,10 @@ hipError_t launch_fwd_mfma(const Params& p, int32_t max_list_len, void* ws, hipS
   } else {
     blocks = (unsigned)tiles * p.Hkv;
   }
-  hipError_t e = launch_kv_layout(p, max_list_len, FW_IMG_KINDS, ws, st);
+  hipError_t e = launch_kv_layout(p, max_list_len, ws, st);
   if (e != hipSuccess) return e;
   const unsigned char* k_img = (const unsigned char*)ws;
-  const unsigned char* vt_img = k_img + kv_image_bytes(p, max_list_len, FW_IMG_KINDS) / 2;
+  const unsigned char* vt_img = k_img + kv_image_bytes(p, max_list_len) / 2;
   { ProfScope prof_("attn_fwd_mfma", st); fwd_mfma_kernel<<<dim3(blocks), dim3(FW_THREADS), FW_LDS, st>>>(p, tiles, xcd_map, k_img, vt_img, 2 * max_list_len); }
   return hipGetLastError();
 }

@@ -40,8 +40,8 @@ hipError_t launch_fwd_generic(const Params& p, bool is_bf16, hipStream_t st);
 hipError_t launch_bwd_generic(const Params& p, bool is_bf16, int32_t max_list_len, hipStream_t st);
 
 // kv_layout.hip: LDS-ordered images of the selected pages
-size_t kv_image_bytes(const Params& p, int32_t max_len, int kinds);
-hipError_t launch_kv_layout(const Params& p, int32_t max_len, int kinds, void* img, hipStream_t st);
+size_t kv_image_bytes(const Params& p, int32_t max_len);
+hipError_t launch_kv_layout(const Params& p, int32_t max_len, void* img, hipStream_t st);
 
 // attn_fwd_mfma.hip, attn_bwd_mfma.hip, attn_bwd_dkv_mfma.hip: the matrix-core kernels
 bool mfma_supported(const Params& p, bool is_bf16);
