@@ -82,8 +82,9 @@ def test_strided_views_are_honoured():
 
 
 def test_strided_views_are_honoured_by_the_mfma_kernels():
-    """The same with bf16 tensors (MFMA kernels, page and row-space images, direct global -> LDS copies):
-    Q / O / dO / dQ rows and pool rows padded by 8 elements, bf16 gradient pool."""
+    """The same with bf16 tensors (MFMA kernels: page images of the forward, direct global -> LDS copies of
+    pool rows and of Q / dO rows in the backward): Q / O / dO / dQ rows and pool rows padded by 8 elements,
+    bf16 gradient pool."""
     w = Workload("bf16_strided", 14, 2, 128, 128, 256, 128 * 11, 3, "bf16", "bf16", 0.0884, extra_phys=2, seed=41)
     x = make_inputs(w, "cuda")
     hx = pu.host_inputs(x)
