@@ -153,3 +153,21 @@ def test_mfma_bf16_nonzero_pool_and_single_local_page():
     w = Workload("bf16_g1", 2, 2, 128, 128, 128, 512, 2, "bf16", "f32", 0.0884, seed=31)
     rep = pu.full_parity(w, init_grad=0.5)
     _show(w.name, rep)
+
+
+# Stage counts of the dK/dV kernel around its ring of four stage buffers (a slice of a page visits
+# (C / 32) G / 2 / n_split 64-row stages, fewer on the causal diagonal): slices of 0 / 1 stages, of 1 / 2,
+# of 5 (the ring wraps), and two stages per workgroup with the pool updated in place (one slice).
+RING_CASES = [
+    Workload("bf16_ring_1", 4, 4, 128, 128, 256, 128 * 8, 2, "bf16", "f32", 0.0884, seed=51),
+    Workload("bf16_ring_1_2", 6, 2, 128, 128, 128, 128 * 5, None, "bf16", "bf16", 0.0884, seed=52),
+    Workload("bf16_ring_5", 2, 1, 128, 128, 640, 128 * 9, 2, "bf16", "f32", 0.0884, seed=53),
+    Workload("bf16_ring_in_place", 4, 4, 128, 128, 128, 128 * 512, None, "bf16", "f32", 0.0884, seed=54),
+]
+
+
+@pytest.mark.parametrize("w", RING_CASES, ids=lambda w: w.name)
+def test_mfma_bf16_stage_ring_edges(w):
+    with pu.kernels_ran(pu.MFMA_KERNELS):
+        rep = pu.full_parity(w, init_grad=0.25)
+    _show(w.name, rep)
