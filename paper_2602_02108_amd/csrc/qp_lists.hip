@@ -2,9 +2,9 @@
 // tokens pick that page's own top-K key pages).  The attention kernels need three
 // things that the lists do not give directly, all derived here on the device, once per
 // call, without atomics on anything that reaches a result:
-//   * the union of a KV head's lists (ascending): the pages whose K/V images are laid
-//     out, and the pages that one dK/dV workgroup each owns;
-//   * for every list entry its position in that union (where its image sits);
+//   * the union of a KV head's lists (ascending): the pages whose K/V images the forward
+//     lays out, and the pages that one dK/dV workgroup each owns;
+//   * for every list entry its position in that union (where the forward finds its image);
 //   * for every union page the query pages whose list holds it (inverse lists, CSR,
 //     ascending), cut into dK/dV work units of at most QP_SLICE query pages; a page cut
 //     into several units gets partial-sum slots, added to the pool in a fixed order.  The
